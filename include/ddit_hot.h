@@ -1,0 +1,192 @@
+/*
+ * libddit_hot - the DiT denoising step eps_theta(x_t, t, c) of a text-to-video
+ * diffusion transformer (paper eq. 1), as hand-written HIP kernels for gfx950.
+ *
+ * The model is the spatial-temporal DiT of the paper's section 2.2: three kinds of
+ * Transformer blocks, "spatial" (tokens sharing a temporal index attend to each
+ * other), "temporal" (tokens sharing a spatial location attend across time) and
+ * "cross-attention" (every token attends to the text condition).  Table 1 names it
+ * (STDiT-v3, 1.1 B parameters).  One *layer* here is
+ *     x += gate_msa * Wo . SelfAttn(QKV(modulate(LN(x), shift_msa, scale_msa)))
+ *     x +=            Wco . CrossAttn(Wcq x, Wckv y, valid_len)
+ *     x += gate_mlp * W2 . GELU_tanh(W1 modulate(LN(x), shift_mlp, scale_mlp))
+ * with SelfAttn spatial or temporal; one *block* is a spatial layer followed by a
+ * temporal layer; a denoising step is the timestep conditioning followed by
+ * n_blocks blocks.  (shift, scale, gate) x (msa, mlp) are the six D-vectors of
+ * table_l[6,D] + c6[b], c6 = W_ada SiLU(temb) + b_ada (adaLN-single).
+ *
+ * Conventions for every entry point
+ *  - Token order: x[B,T,S,D], token n = (b*T + t)*S + s, S = Hp*Wp.  Text y[B,Ly,D].
+ *  - All data pointers are DEVICE pointers unless the name ends in _host.
+ *    Activations and weights are bf16 (the upper 16 bits of an IEEE fp32), row
+ *    major; a Linear's weight is [out,in] and computes u W^T + b.  The adaLN table,
+ *    c6 and lse are fp32.  Every device pointer must be 16-byte aligned and every
+ *    leading dimension a multiple of 8 elements.
+ *  - Ownership: the caller owns every buffer including the workspace; the library
+ *    allocates and frees no device memory and keeps no state between calls.
+ *    Buffers must stay alive until `hip_stream` has run past the call.
+ *  - Asynchrony: all work is enqueued on `hip_stream` (a hipStream_t, NULL = the
+ *    default stream); no call synchronises with the host.  *_host arrays are read
+ *    before the call returns.
+ *  - Errors: the return value is DDIT_OK (0) or a negative ddit_status.  Arguments
+ *    are validated before anything is enqueued; on error nothing has been launched
+ *    (except DDIT_ERR_HIP, raised by a failing launch).  ddit_last_error() gives a
+ *    thread-local description.  Nothing throws or aborts across this boundary.
+ *  - Arithmetic: bf16 storage, fp32 accumulation; the residual stream is fp32
+ *    inside ddit_stdit_block_fwd and ddit_denoise_step and is rounded to bf16 once,
+ *    at the output.
+ */
+#ifndef DDIT_HOT_H
+#define DDIT_HOT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DDIT_ABI_VERSION 1u
+
+typedef enum {
+  DDIT_OK = 0,
+  DDIT_ERR_INVALID_ARG = -1, /* NULL required pointer, non-positive size, valid_len outside [1,Ly] */
+  DDIT_ERR_UNSUPPORTED = -2, /* a shape the kernels do not cover (message names the field) */
+  DDIT_ERR_WORKSPACE = -3,   /* workspace NULL or smaller than ddit_workspace_bytes() */
+  DDIT_ERR_ALIGNMENT = -4,   /* pointer not 16-byte aligned / leading dimension not a multiple of 8 */
+  DDIT_ERR_HIP = -5          /* a HIP launch failed; message carries hipGetErrorString() */
+} ddit_status;
+
+typedef enum { DDIT_ATTN_SPATIAL = 0, DDIT_ATTN_TEMPORAL = 1, DDIT_ATTN_CROSS = 2 } ddit_attn_kind;
+
+/* flags of ddit_shape */
+#define DDIT_FLAG_TAPS 1u /* block/step: keep per-branch intermediates of the LAST layer pair run
+                             (see ddit_tap_region) in the tail of the workspace, for tests */
+
+/* Problem shape.  Supported: dh in {64, 72}; D, A = H*dh, M, multiples of 8; A <= D
+ * (A < D is one rank's share of a head-split sequence-parallel run); B <= 64. */
+typedef struct {
+  uint32_t struct_size; /* sizeof(ddit_shape): versions the struct */
+  uint32_t flags;
+  int32_t B, T, Hp, Wp;              /* S = Hp*Wp tokens per frame, L = T*S per sample */
+  int32_t D, H, dh, M, Ly, n_blocks; /* hidden, heads, head dim, MLP width, text tokens, blocks */
+  float ln_eps;                      /* LayerNorm epsilon (1e-6) */
+} ddit_shape;
+
+/* One layer's parameters.  bf16 [out,in] weights; a bias may be NULL (= zero).
+ * w_qkv rows are ordered q (all heads) | k | v, head h owning rows h*dh..(h+1)*dh-1 of
+ * each group; w_ckv rows are k | v.  ada_table is fp32 [6,D] in the order shift_msa,
+ * scale_msa, gate_msa, shift_mlp, scale_mlp, gate_mlp. */
+typedef struct {
+  const void *w_qkv, *b_qkv; /* [3A,D], [3A] */
+  const void *w_o, *b_o;     /* [D,A],  [D]  */
+  const void *w_cq, *b_cq;   /* [A,D],  [A]  */
+  const void *w_ckv, *b_ckv; /* [2A,D], [2A] */
+  const void *w_co, *b_co;   /* [D,A],  [D]  */
+  const void *w_fc1, *b_fc1; /* [M,D],  [M]  */
+  const void *w_fc2, *b_fc2; /* [D,M],  [D]  */
+  const float *ada_table;    /* [6,D] fp32 */
+} ddit_layer_weights;
+
+typedef struct {
+  ddit_layer_weights spatial, temporal;
+} ddit_block_weights;
+
+/* Timestep conditioning: e = [cos(t f_i), sin(t f_i)], f_i = 10000^(-i/128), i < 128;
+ * temb = W_t2 SiLU(W_t1 e + b_t1) + b_t2;  c6 = W_ada SiLU(temb) + b_ada. */
+typedef struct {
+  const void *w_t1, *b_t1;          /* [D,256], [D] */
+  const void *w_t2, *b_t2;          /* [D,D],   [D] */
+  const void *w_ada, *b_ada;        /* [6D,D],  [6D] */
+  const ddit_block_weights *blocks; /* HOST array of n_blocks entries (holding device pointers) */
+} ddit_step_weights;
+
+uint32_t ddit_abi_version(void);
+const char *ddit_status_string(int status);
+const char *ddit_last_error(void); /* thread-local, never NULL */
+
+/* Bytes of workspace ddit_stdit_block_fwd / ddit_denoise_step / ddit_attn_fwd need for
+ * this shape (with DDIT_FLAG_TAPS: including the tap area). */
+int ddit_workspace_bytes(const ddit_shape *shape, size_t *bytes_out);
+
+/* Where a tap lives, when DDIT_FLAG_TAPS is set: offset from the start of the workspace
+ * and size in bytes.  layer: 0 = spatial layer, 1 = temporal layer of the last block run.
+ * tap ids: */
+typedef enum {
+  DDIT_TAP_XH_MSA = 0,      /* bf16 [N,D]  modulate(LN(x)) feeding QKV            */
+  DDIT_TAP_QKV = 1,         /* bf16 [N,3A] q | k | v                               */
+  DDIT_TAP_O = 2,           /* bf16 [N,A]  self-attention output                   */
+  DDIT_TAP_X_AFTER_ATTN = 3,  /* fp32 [N,D] stream after the gated attention add   */
+  DDIT_TAP_QC = 4,          /* bf16 [N,A]  cross-attention queries                 */
+  DDIT_TAP_KVC = 5,         /* bf16 [B*Ly,2A] cross-attention k | v                */
+  DDIT_TAP_OC = 6,          /* bf16 [N,A]  cross-attention output                  */
+  DDIT_TAP_X_AFTER_CROSS = 7, /* fp32 [N,D]                                        */
+  DDIT_TAP_XH_MLP = 8,      /* bf16 [N,D]                                          */
+  DDIT_TAP_H = 9,           /* bf16 [N,M]  GELU(fc1)                               */
+  DDIT_TAP_X_OUT = 10,      /* fp32 [N,D]  stream after the layer                  */
+  DDIT_TAP_COUNT = 11
+} ddit_tap_id;
+int ddit_tap_region(const ddit_shape *shape, int layer, int tap, size_t *offset_out, size_t *bytes_out);
+
+/* Exact softmax attention, O = softmax(Q K^T / sqrt(dh)) V (section 2.2: which tokens
+ * attend to which is fixed by `kind`).
+ *   SPATIAL : q,k,v,o are [B,T,S,H,dh]; for each (b,t,h) the S tokens of frame t.
+ *   TEMPORAL: same tensors; for each (b,s,h) the T tokens at location s.
+ *   CROSS   : q,o [B,L,H,dh], k,v [B,Ly,H,dh]; keys j >= kv_valid_len_host[b] take no part.
+ * ld_* are the row (token) strides in elements, >= H*dh: q, k and v may be column
+ * slices of one fused projection buffer.  kv_valid_len_host: HOST int32[B] or NULL
+ * (= Ly), CROSS only, each in [1,Ly].  lse_or_null: optional fp32 [tokens,H] receiving
+ * log(sum_j exp(score_ij)) of the scaled scores.  Uses no workspace today; the
+ * arguments are reserved (may be NULL/0). */
+int ddit_attn_fwd(ddit_attn_kind kind, const ddit_shape *shape, const void *q, const void *k, const void *v,
+                  int64_t ld_q, int64_t ld_kv, const int32_t *kv_valid_len_host, void *o, int64_t ld_o,
+                  float *lse_or_null, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* One block (spatial layer then temporal layer) on x_in bf16 [B,T,S,D] with text y bf16
+ * [B,Ly,D], valid lengths (HOST int32[B] or NULL = Ly) and conditioning c6 (device fp32
+ * [B,6D]).  x_out bf16 [B,T,S,D] may alias x_in.  shape->n_blocks is ignored. */
+int ddit_stdit_block_fwd(const ddit_shape *shape, const ddit_block_weights *weights, const void *x_in,
+                         const void *y, const int32_t *y_valid_len_host, const float *c6, void *x_out,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* One denoising step in token space: conditioning from timesteps_host (HOST fp32[B]),
+ * then shape->n_blocks blocks with an fp32 residual stream, rounded to bf16 at x_out.
+ * If temb_or_null (device fp32 [B,D]) is given it replaces the timestep embedder's
+ * output (timesteps_host may then be NULL). */
+int ddit_denoise_step(const ddit_shape *shape, const ddit_step_weights *weights, const void *x_in,
+                      const void *y, const int32_t *y_valid_len_host, const float *timesteps_host,
+                      const float *temb_or_null, void *x_out, void *workspace, size_t workspace_bytes,
+                      void *hip_stream);
+
+/* ---- single stages of the path, exported for kernel-level parity tests and profiling ---- */
+
+/* out[n,:] = bf16( LN(x[n,:]) * (1 + scale_b) + shift_b ), LN without affine over D with
+ * biased variance; (shift_b, scale_b) = rows (3*which, 3*which+1) of ada_table + c6[b],
+ * which = 0 (msa) or 1 (mlp), b = n / tokens_per_sample.  x fp32 [N,D], out bf16 [N,D]. */
+int ddit_modulated_layernorm_fwd(const float *x, const float *ada_table, const float *c6, int which,
+                                 int64_t N, int64_t tokens_per_sample, int32_t D, float eps, void *out,
+                                 void *hip_stream);
+
+typedef enum {
+  DDIT_EPI_BF16 = 0,          /* out bf16 [N,n] = u W^T + b                                        */
+  DDIT_EPI_GELU_BF16 = 1,     /* out bf16 = GELU_tanh(u W^T + b)                                    */
+  DDIT_EPI_RESIDUAL_F32 = 2   /* resid fp32 [N,n] += gate_b * (u W^T + b); gate_b = row gate_row of
+                                 ada_table + c6[b] (gate_row < 0: no gate); if out != NULL it also
+                                 receives bf16(resid)                                               */
+} ddit_epilogue;
+
+/* u bf16 [N,k] (row stride ld_u), W bf16 [n,k], bias bf16 [n] or NULL. */
+int ddit_linear_fwd(int epilogue, const void *u, int64_t ld_u, const void *W, const void *bias, int64_t N,
+                    int32_t n, int32_t k, void *out, int64_t ld_out, float *resid, const float *ada_table,
+                    const float *c6, int gate_row, int64_t tokens_per_sample, void *hip_stream);
+
+/* c6 fp32 [B,6D] from timesteps (HOST fp32[B]) or from a given temb (device fp32 [B,D]).
+ * scratch: device fp32, at least B*(256 + 2*D) floats. */
+int ddit_timestep_conditioning(const ddit_shape *shape, const ddit_step_weights *weights,
+                               const float *timesteps_host, const float *temb_or_null, float *c6_out,
+                               float *scratch, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDIT_HOT_H */

@@ -1,0 +1,219 @@
+"""ctypes binding of libddit_hot: one Python function per C entry point, same names.
+
+Argument marshalling only (tensor -> pointer, dataclass -> struct); every step of the
+path runs inside the library's HIP kernels.  There is no fallback: if the shared
+library is missing or fails to load, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libddit_hot.so")
+
+DDIT_OK = 0
+DDIT_ERR_INVALID_ARG, DDIT_ERR_UNSUPPORTED, DDIT_ERR_WORKSPACE, DDIT_ERR_ALIGNMENT, DDIT_ERR_HIP = -1, -2, -3, -4, -5
+DDIT_ATTN_SPATIAL, DDIT_ATTN_TEMPORAL, DDIT_ATTN_CROSS = 0, 1, 2
+DDIT_EPI_BF16, DDIT_EPI_GELU_BF16, DDIT_EPI_RESIDUAL_F32 = 0, 1, 2
+DDIT_FLAG_TAPS = 1
+TAP_NAMES = ["xh_msa", "qkv", "o", "x_after_attn", "qc", "kvc", "oc", "x_after_cross", "xh_mlp", "h", "x_out"]
+_TAP_DTYPE = {"x_after_attn": torch.float32, "x_after_cross": torch.float32, "x_out": torch.float32}
+
+EXPORTS = ["ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_workspace_bytes", "ddit_tap_region",
+           "ddit_attn_fwd", "ddit_stdit_block_fwd", "ddit_denoise_step", "ddit_modulated_layernorm_fwd",
+           "ddit_linear_fwd", "ddit_timestep_conditioning"]
+
+
+class ddit_shape(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("flags", C.c_uint32),
+                ("B", C.c_int32), ("T", C.c_int32), ("Hp", C.c_int32), ("Wp", C.c_int32),
+                ("D", C.c_int32), ("H", C.c_int32), ("dh", C.c_int32), ("M", C.c_int32),
+                ("Ly", C.c_int32), ("n_blocks", C.c_int32), ("ln_eps", C.c_float)]
+
+
+_LAYER_FIELDS = ["w_qkv", "b_qkv", "w_o", "b_o", "w_cq", "b_cq", "w_ckv", "b_ckv", "w_co", "b_co",
+                 "w_fc1", "b_fc1", "w_fc2", "b_fc2", "ada_table"]
+
+
+class ddit_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _LAYER_FIELDS]
+
+
+class ddit_block_weights(C.Structure):
+    _fields_ = [("spatial", ddit_layer_weights), ("temporal", ddit_layer_weights)]
+
+
+class ddit_step_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w_t1", "b_t1", "w_t2", "b_t2", "w_ada", "b_ada")] + \
+               [("blocks", C.POINTER(ddit_block_weights))]
+
+
+class DditError(RuntimeError):
+    def __init__(self, status: int, detail: str):
+        super().__init__("libddit_hot status %d: %s" % (status, detail))
+        self.status = status
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libddit_hot.so is not built (%s): run `python -m paper_2506_13497_amd.build` or "
+                          "__graft_entry__.build(); there is no fallback path" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    lib.ddit_abi_version.restype = C.c_uint32
+    lib.ddit_status_string.restype = C.c_char_p
+    lib.ddit_status_string.argtypes = [C.c_int]
+    lib.ddit_last_error.restype = C.c_char_p
+    lib.ddit_workspace_bytes.argtypes = [C.POINTER(ddit_shape), C.POINTER(C.c_size_t)]
+    lib.ddit_tap_region.argtypes = [C.POINTER(ddit_shape), C.c_int, C.c_int, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+    lib.ddit_attn_fwd.argtypes = [C.c_int, C.POINTER(ddit_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                  C.c_int64, C.POINTER(C.c_int32), C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                  C.c_size_t, C.c_void_p]
+    lib.ddit_stdit_block_fwd.argtypes = [C.POINTER(ddit_shape), C.POINTER(ddit_block_weights), C.c_void_p, C.c_void_p,
+                                         C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                         C.c_void_p]
+    lib.ddit_denoise_step.argtypes = [C.POINTER(ddit_shape), C.POINTER(ddit_step_weights), C.c_void_p, C.c_void_p,
+                                      C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_size_t, C.c_void_p]
+    lib.ddit_modulated_layernorm_fwd.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64,
+                                                 C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
+    lib.ddit_linear_fwd.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                    C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                    C.c_int64, C.c_void_p]
+    lib.ddit_timestep_conditioning.argtypes = [C.POINTER(ddit_shape), C.POINTER(ddit_step_weights),
+                                               C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    for n in EXPORTS:
+        if n not in ("ddit_abi_version", "ddit_status_string", "ddit_last_error"):
+            getattr(lib, n).restype = C.c_int
+    return lib
+
+
+_lib = _load()
+
+
+def _check(rc: int) -> None:
+    if rc != DDIT_OK:
+        raise DditError(rc, (_lib.ddit_last_error() or b"").decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_shape(B, T, Hp, Wp, D, H, dh, M, Ly, n_blocks, flags=0, ln_eps=1e-6) -> ddit_shape:
+    return ddit_shape(C.sizeof(ddit_shape), flags, B, T, Hp, Wp, D, H, dh, M, Ly, n_blocks, ln_eps)
+
+
+def _i32(vals: Optional[Sequence[int]]):
+    if vals is None:
+        return None
+    return (C.c_int32 * len(vals))(*[int(v) for v in vals])
+
+
+def layer_struct(w: Dict[str, torch.Tensor]) -> ddit_layer_weights:
+    s = ddit_layer_weights()
+    for n in _LAYER_FIELDS:
+        t = w.get(n)
+        setattr(s, n, None if t is None else t.data_ptr())
+    return s
+
+
+def block_struct(wb: Dict[str, Dict[str, torch.Tensor]]) -> ddit_block_weights:
+    return ddit_block_weights(layer_struct(wb["spatial"]), layer_struct(wb["temporal"]))
+
+
+def step_struct(sw: Dict[str, torch.Tensor], blocks: List[Dict[str, Dict[str, torch.Tensor]]]):
+    arr = (ddit_block_weights * max(len(blocks), 1))()
+    for i, wb in enumerate(blocks):
+        arr[i] = block_struct(wb)
+    s = ddit_step_weights()
+    for n in ("w_t1", "b_t1", "w_t2", "b_t2", "w_ada", "b_ada"):
+        t = sw.get(n)
+        setattr(s, n, None if t is None else t.data_ptr())
+    s.blocks = C.cast(arr, C.POINTER(ddit_block_weights))
+    s._keep = arr  # keep the host array alive with the struct
+    return s
+
+
+# ----------------------------------------------------------------------------- entry points
+def ddit_abi_version() -> int:
+    return int(_lib.ddit_abi_version())
+
+
+def ddit_status_string(status: int) -> str:
+    return _lib.ddit_status_string(status).decode()
+
+
+def ddit_last_error() -> str:
+    return (_lib.ddit_last_error() or b"").decode()
+
+
+def ddit_workspace_bytes(shape: ddit_shape) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.ddit_workspace_bytes(C.byref(shape), C.byref(n)))
+    return int(n.value)
+
+
+def ddit_tap_region(shape: ddit_shape, layer: int, tap: int):
+    off, nb = C.c_size_t(0), C.c_size_t(0)
+    _check(_lib.ddit_tap_region(C.byref(shape), layer, tap, C.byref(off), C.byref(nb)))
+    return int(off.value), int(nb.value)
+
+
+def ddit_attn_fwd(kind: int, shape: ddit_shape, q, k, v, ld_q: int, ld_kv: int, kv_valid_len, o, ld_o: int,
+                  lse=None, workspace=None) -> None:
+    _check(_lib.ddit_attn_fwd(kind, C.byref(shape), _ptr(q), _ptr(k), _ptr(v), ld_q, ld_kv, _i32(kv_valid_len),
+                              _ptr(o), ld_o, _ptr(lse), _ptr(workspace),
+                              0 if workspace is None else workspace.numel() * workspace.element_size(), _stream()))
+
+
+def ddit_stdit_block_fwd(shape: ddit_shape, weights: ddit_block_weights, x_in, y, y_valid_len, c6, x_out,
+                         workspace) -> None:
+    _check(_lib.ddit_stdit_block_fwd(C.byref(shape), C.byref(weights), _ptr(x_in), _ptr(y), _i32(y_valid_len),
+                                     _ptr(c6), _ptr(x_out), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream()))
+
+
+def ddit_denoise_step(shape: ddit_shape, weights: ddit_step_weights, x_in, y, y_valid_len, timesteps, temb, x_out,
+                      workspace) -> None:
+    ts = None if timesteps is None else (C.c_float * len(timesteps))(*[float(t) for t in timesteps])
+    _check(_lib.ddit_denoise_step(C.byref(shape), C.byref(weights), _ptr(x_in), _ptr(y), _i32(y_valid_len), ts,
+                                  _ptr(temb), _ptr(x_out), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream()))
+
+
+def ddit_modulated_layernorm_fwd(x, ada_table, c6, which: int, tokens_per_sample: int, eps: float, out) -> None:
+    N, D = x.shape[0], x.shape[1]
+    _check(_lib.ddit_modulated_layernorm_fwd(_ptr(x), _ptr(ada_table), _ptr(c6), which, N, tokens_per_sample, D, eps,
+                                             _ptr(out), _stream()))
+
+
+def ddit_linear_fwd(epilogue: int, u, ld_u: int, W, bias, N: int, n: int, k: int, out, ld_out: int, resid=None,
+                    ada_table=None, c6=None, gate_row: int = -1, tokens_per_sample: int = 1) -> None:
+    _check(_lib.ddit_linear_fwd(epilogue, _ptr(u), ld_u, _ptr(W), _ptr(bias), N, n, k, _ptr(out), ld_out,
+                                _ptr(resid), _ptr(ada_table), _ptr(c6), gate_row, tokens_per_sample, _stream()))
+
+
+def ddit_timestep_conditioning(shape: ddit_shape, weights: ddit_step_weights, timesteps, temb, c6_out, scratch) -> None:
+    ts = None if timesteps is None else (C.c_float * len(timesteps))(*[float(t) for t in timesteps])
+    _check(_lib.ddit_timestep_conditioning(C.byref(shape), C.byref(weights), ts, _ptr(temb), _ptr(c6_out),
+                                           _ptr(scratch), _stream()))
+
+
+# ----------------------------------------------------------------------------- helpers (no arithmetic)
+def alloc_workspace(shape: ddit_shape, device="cuda") -> torch.Tensor:
+    return torch.empty(ddit_workspace_bytes(shape), dtype=torch.uint8, device=device)
+
+
+def read_tap(shape: ddit_shape, workspace: torch.Tensor, layer: int, name: str) -> torch.Tensor:
+    """View of one tap region of the workspace as a flat tensor of its dtype."""
+    off, nb = ddit_tap_region(shape, layer, TAP_NAMES.index(name))
+    raw = workspace[off:off + nb]
+    return raw.view(_TAP_DTYPE.get(name, torch.bfloat16))

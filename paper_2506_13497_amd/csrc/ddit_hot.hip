@@ -1,0 +1,441 @@
+// C ABI of libddit_hot: argument validation, workspace carving and the sequencing of the
+// kernels of one STDiT layer / block / denoising step on the caller's HIP stream.
+// Nothing here allocates device memory or synchronises with the host.
+#include "../../include/ddit_hot.h"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "ddit_common.hpp"
+
+namespace ddit {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int hip_fail(hipError_t e, const char *what) {
+  if (e == hipSuccess) return DDIT_OK;
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return DDIT_ERR_HIP;
+}
+
+namespace {
+
+inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Dims {
+  int64_t B, T, S, L, N, D, H, dh, A, M, Ly;
+};
+
+struct Layout {
+  size_t x, xh, qkv, o, kvc, h, c6, cond, taps, total;
+  size_t tap_off[2][DDIT_TAP_COUNT], tap_bytes[DDIT_TAP_COUNT];
+};
+
+int check_shape(const ddit_shape *sh, Dims *d) {
+  if (!sh) { set_error("shape is NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (sh->struct_size != sizeof(ddit_shape)) {
+    set_error("shape->struct_size=%u, this library expects %zu", sh->struct_size, sizeof(ddit_shape));
+    return DDIT_ERR_INVALID_ARG;
+  }
+  if (sh->B < 1 || sh->T < 1 || sh->Hp < 1 || sh->Wp < 1 || sh->D < 1 || sh->H < 1 || sh->dh < 1 || sh->M < 1 ||
+      sh->Ly < 1 || sh->n_blocks < 0) {
+    set_error("shape: every extent must be positive (B=%d T=%d Hp=%d Wp=%d D=%d H=%d dh=%d M=%d Ly=%d n_blocks=%d)",
+              sh->B, sh->T, sh->Hp, sh->Wp, sh->D, sh->H, sh->dh, sh->M, sh->Ly, sh->n_blocks);
+    return DDIT_ERR_INVALID_ARG;
+  }
+  if (!(sh->ln_eps > 0.f)) { set_error("shape->ln_eps must be positive"); return DDIT_ERR_INVALID_ARG; }
+  if (sh->dh != 64 && sh->dh != 72) { set_error("dh=%d: supported head dims are 64 and 72", sh->dh); return DDIT_ERR_UNSUPPORTED; }
+  if (sh->B > 64) { set_error("B=%d: at most 64 samples per call", sh->B); return DDIT_ERR_UNSUPPORTED; }
+  const int64_t A = (int64_t)sh->H * sh->dh;
+  if (A > sh->D) { set_error("H*dh=%lld exceeds D=%d", (long long)A, sh->D); return DDIT_ERR_UNSUPPORTED; }
+  if (sh->D % 8 || sh->M % 8) { set_error("D=%d and M=%d must be multiples of 8", sh->D, sh->M); return DDIT_ERR_UNSUPPORTED; }
+  if (sh->D > 4096) { set_error("D=%d: hidden size above 4096 is not supported", sh->D); return DDIT_ERR_UNSUPPORTED; }
+  d->B = sh->B; d->T = sh->T; d->S = (int64_t)sh->Hp * sh->Wp; d->L = d->T * d->S; d->N = d->B * d->L;
+  d->D = sh->D; d->H = sh->H; d->dh = sh->dh; d->A = A; d->M = sh->M; d->Ly = sh->Ly;
+  if (d->N > (int64_t)1 << 30) { set_error("B*T*S=%lld tokens: too many", (long long)d->N); return DDIT_ERR_UNSUPPORTED; }
+  return DDIT_OK;
+}
+
+void make_layout(const Dims &d, uint32_t flags, Layout *lo) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  lo->x = take((size_t)d.N * d.D * 4);
+  lo->xh = take((size_t)d.N * d.D * 2);
+  lo->qkv = take((size_t)d.N * 3 * d.A * 2);
+  lo->o = take((size_t)d.N * d.A * 2);
+  lo->kvc = take((size_t)d.B * d.Ly * 2 * d.A * 2);
+  lo->h = take((size_t)d.N * d.M * 2);
+  lo->c6 = take((size_t)d.B * 6 * d.D * 4);
+  lo->cond = take((size_t)d.B * (256 + 2 * d.D) * 4);
+  lo->taps = off;
+  const size_t ND = (size_t)d.N * d.D, NA = (size_t)d.N * d.A;
+  const size_t tb[DDIT_TAP_COUNT] = {ND * 2, 3 * NA * 2, NA * 2, ND * 4, NA * 2, (size_t)d.B * d.Ly * 2 * d.A * 2,
+                                     NA * 2, ND * 4, ND * 2, (size_t)d.N * d.M * 2, ND * 4};
+  for (int t = 0; t < DDIT_TAP_COUNT; ++t) lo->tap_bytes[t] = tb[t];
+  if (flags & DDIT_FLAG_TAPS) {
+    for (int l = 0; l < 2; ++l)
+      for (int t = 0; t < DDIT_TAP_COUNT; ++t) lo->tap_off[l][t] = take(tb[t]);
+  }
+  lo->total = off;
+}
+
+int check_valid_len(const int32_t *vl, const Dims &d) {
+  if (!vl) return DDIT_OK;
+  for (int b = 0; b < d.B; ++b)
+    if (vl[b] < 1 || vl[b] > d.Ly) {
+      set_error("valid_len[%d]=%d outside [1,%lld]", b, vl[b], (long long)d.Ly);
+      return DDIT_ERR_INVALID_ARG;
+    }
+  return DDIT_OK;
+}
+
+int check_layer_weights(const ddit_layer_weights &w, const char *which) {
+  const void *req[] = {w.w_qkv, w.w_o, w.w_cq, w.w_ckv, w.w_co, w.w_fc1, w.w_fc2, w.ada_table};
+  const char *names[] = {"w_qkv", "w_o", "w_cq", "w_ckv", "w_co", "w_fc1", "w_fc2", "ada_table"};
+  for (int i = 0; i < 8; ++i)
+    if (!req[i]) { set_error("%s.%s is NULL", which, names[i]); return DDIT_ERR_INVALID_ARG; }
+  const void *all[] = {w.w_qkv, w.b_qkv, w.w_o, w.b_o, w.w_cq, w.b_cq, w.w_ckv, w.b_ckv,
+                       w.w_co, w.b_co, w.w_fc1, w.b_fc1, w.w_fc2, w.b_fc2, w.ada_table};
+  for (const void *p : all)
+    if (p && !aligned16(p)) { set_error("%s: a weight pointer is not 16-byte aligned", which); return DDIT_ERR_ALIGNMENT; }
+  return DDIT_OK;
+}
+
+int run_attention(ddit_attn_kind kind, const Dims &d, const void *q, const void *k, const void *v, int64_t ld_q,
+                  int64_t ld_kv, const int32_t *valid_len, void *o, int64_t ld_o, float *lse, hipStream_t s) {
+  AttnArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+  a.ld_q = ld_q; a.ld_kv = ld_kv; a.ld_o = ld_o;
+  a.H = (int)d.H; a.dh = (int)d.dh;
+  switch (kind) {
+    case DDIT_ATTN_SPATIAL:
+      a.n_groups = (int)(d.B * d.T); a.g_inner = 1;
+      a.q_outer = a.kv_outer = d.S; a.q_inner = a.kv_inner = 0;
+      a.q_tok_step = a.kv_tok_step = 1;
+      a.Lq = a.Lk_max = (int)d.S;
+      break;
+    case DDIT_ATTN_TEMPORAL:
+      a.n_groups = (int)(d.B * d.S); a.g_inner = (int)d.S;
+      a.q_outer = a.kv_outer = d.T * d.S; a.q_inner = a.kv_inner = 1;
+      a.q_tok_step = a.kv_tok_step = d.S;
+      a.Lq = a.Lk_max = (int)d.T;
+      break;
+    case DDIT_ATTN_CROSS:
+      a.n_groups = (int)d.B; a.g_inner = 1;
+      a.q_outer = d.L; a.kv_outer = d.Ly; a.q_inner = a.kv_inner = 0;
+      a.q_tok_step = a.kv_tok_step = 1;
+      a.Lq = (int)d.L; a.Lk_max = (int)d.Ly;
+      if (valid_len) {
+        a.use_kv_len = 1;
+        for (int b = 0; b < d.B; ++b) a.kv_len[b] = valid_len[b];
+      }
+      break;
+    default:
+      set_error("unknown attention kind %d", (int)kind);
+      return DDIT_ERR_INVALID_ARG;
+  }
+  return launch_flash_attn(a, s);
+}
+
+struct Taps {
+  bool on; unsigned char *ws; const Layout *lo; int layer; hipStream_t s;
+  int keep(int tap, const void *src) const {
+    if (!on) return DDIT_OK;
+    return hip_fail(hipMemcpyAsync(ws + lo->tap_off[layer][tap], src, lo->tap_bytes[tap], hipMemcpyDeviceToDevice, s),
+                    "tap copy");
+  }
+};
+
+#define DDIT_TRY(expr) do { int rc_ = (expr); if (rc_ != DDIT_OK) return rc_; } while (0)
+
+// One layer on the fp32 stream x (in the workspace).
+int run_layer(ddit_attn_kind kind, const Dims &d, const ddit_layer_weights &w, const void *y, const int32_t *valid_len,
+              const float *c6, float eps, unsigned char *ws, const Layout &lo, const Taps &tp, hipStream_t s) {
+  float *x = reinterpret_cast<float *>(ws + lo.x);
+  void *xh = ws + lo.xh;
+  unsigned char *qkv = ws + lo.qkv;
+  void *o = ws + lo.o;
+  unsigned char *kvc = ws + lo.kvc;
+  void *h = ws + lo.h;
+  const int64_t N = d.N, D = d.D, A = d.A, M = d.M;
+
+  GemmArgs g;
+  auto base = [&](const void *u, int64_t ld_u, const void *W, const void *b, int64_t rows, int n, int k) {
+    memset(&g, 0, sizeof(g));
+    g.u = u; g.ld_u = ld_u; g.W = W; g.bias = b; g.N = rows; g.n = n; g.k = k; g.tokens_per_sample = d.L;
+  };
+  auto gated = [&](int row) {
+    g.resid = x;
+    if (row >= 0) { g.gate_tab = w.ada_table + (int64_t)row * D; g.gate_c6 = c6 + (int64_t)row * D; g.gate_c6_stride = 6 * D; }
+  };
+
+  // self-attention branch
+  DDIT_TRY(launch_modulated_layernorm(x, w.ada_table, c6, 0, N, d.L, (int)D, eps, xh, s));
+  DDIT_TRY(tp.keep(DDIT_TAP_XH_MSA, xh));
+  base(xh, D, w.w_qkv, w.b_qkv, N, (int)(3 * A), (int)D); g.out = qkv; g.ld_out = 3 * A;
+  DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
+  DDIT_TRY(tp.keep(DDIT_TAP_QKV, qkv));
+  DDIT_TRY(run_attention(kind, d, qkv, qkv + A * 2, qkv + 2 * A * 2, 3 * A, 3 * A, nullptr, o, A, nullptr, s));
+  DDIT_TRY(tp.keep(DDIT_TAP_O, o));
+  base(o, A, w.w_o, w.b_o, N, (int)D, (int)A); gated(2); g.out = xh; g.ld_out = D;   // also xh := bf16(x)
+  DDIT_TRY(launch_gemm(DDIT_EPI_RESIDUAL_F32, g, s));
+  DDIT_TRY(tp.keep(DDIT_TAP_X_AFTER_ATTN, x));
+
+  // cross-attention branch (reads the stream itself; ungated)
+  base(xh, D, w.w_cq, w.b_cq, N, (int)A, (int)D); g.out = qkv; g.ld_out = 3 * A;
+  DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
+  base(y, D, w.w_ckv, w.b_ckv, d.B * d.Ly, (int)(2 * A), (int)D); g.out = kvc; g.ld_out = 2 * A;
+  DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
+  if (tp.on) {  // q_c lives strided inside the qkv buffer: copy it out row by row
+    DDIT_TRY(hip_fail(hipMemcpy2DAsync(tp.ws + lo.tap_off[tp.layer][DDIT_TAP_QC], A * 2, qkv, 3 * A * 2, A * 2, N,
+                                       hipMemcpyDeviceToDevice, s), "tap copy"));
+  }
+  DDIT_TRY(tp.keep(DDIT_TAP_KVC, kvc));
+  DDIT_TRY(run_attention(DDIT_ATTN_CROSS, d, qkv, kvc, kvc + A * 2, 3 * A, 2 * A, valid_len, o, A, nullptr, s));
+  DDIT_TRY(tp.keep(DDIT_TAP_OC, o));
+  base(o, A, w.w_co, w.b_co, N, (int)D, (int)A); gated(-1);
+  DDIT_TRY(launch_gemm(DDIT_EPI_RESIDUAL_F32, g, s));
+  DDIT_TRY(tp.keep(DDIT_TAP_X_AFTER_CROSS, x));
+
+  // MLP branch
+  DDIT_TRY(launch_modulated_layernorm(x, w.ada_table, c6, 1, N, d.L, (int)D, eps, xh, s));
+  DDIT_TRY(tp.keep(DDIT_TAP_XH_MLP, xh));
+  base(xh, D, w.w_fc1, w.b_fc1, N, (int)M, (int)D); g.out = h; g.ld_out = M;
+  DDIT_TRY(launch_gemm(DDIT_EPI_GELU_BF16, g, s));
+  DDIT_TRY(tp.keep(DDIT_TAP_H, h));
+  base(h, M, w.w_fc2, w.b_fc2, N, (int)D, (int)M); gated(5);
+  DDIT_TRY(launch_gemm(DDIT_EPI_RESIDUAL_F32, g, s));
+  DDIT_TRY(tp.keep(DDIT_TAP_X_OUT, x));
+  return DDIT_OK;
+}
+
+int check_common(const Dims &d, const Layout &lo, const void *x_in, const void *y, const void *x_out, void *ws,
+                 size_t ws_bytes) {
+  if (!x_in || !y || !x_out) { set_error("x_in, y and x_out must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (!aligned16(x_in) || !aligned16(y) || !aligned16(x_out)) {
+    set_error("x_in, y and x_out must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT;
+  }
+  if (!ws || ws_bytes < lo.total) {
+    set_error("workspace of %zu bytes given, %zu required", ws ? ws_bytes : (size_t)0, lo.total);
+    return DDIT_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) { set_error("workspace must be 256-byte aligned"); return DDIT_ERR_ALIGNMENT; }
+  (void)d;
+  return DDIT_OK;
+}
+
+}  // namespace
+}  // namespace ddit
+
+using namespace ddit;
+
+extern "C" {
+
+uint32_t ddit_abi_version(void) { return DDIT_ABI_VERSION; }
+
+const char *ddit_status_string(int status) {
+  switch (status) {
+    case DDIT_OK: return "ok";
+    case DDIT_ERR_INVALID_ARG: return "invalid argument";
+    case DDIT_ERR_UNSUPPORTED: return "unsupported shape";
+    case DDIT_ERR_WORKSPACE: return "workspace missing or too small";
+    case DDIT_ERR_ALIGNMENT: return "misaligned pointer or leading dimension";
+    case DDIT_ERR_HIP: return "HIP error";
+  }
+  return "unknown status";
+}
+
+const char *ddit_last_error(void) { return g_err; }
+
+int ddit_workspace_bytes(const ddit_shape *shape, size_t *bytes_out) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  if (!bytes_out) { set_error("bytes_out is NULL"); return DDIT_ERR_INVALID_ARG; }
+  Layout lo;
+  make_layout(d, shape->flags, &lo);
+  *bytes_out = lo.total;
+  return DDIT_OK;
+}
+
+int ddit_tap_region(const ddit_shape *shape, int layer, int tap, size_t *offset_out, size_t *bytes_out) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  if (!(shape->flags & DDIT_FLAG_TAPS)) { set_error("DDIT_FLAG_TAPS is not set in shape->flags"); return DDIT_ERR_INVALID_ARG; }
+  if (layer < 0 || layer > 1 || tap < 0 || tap >= DDIT_TAP_COUNT || !offset_out || !bytes_out) {
+    set_error("tap_region: layer=%d tap=%d out of range or NULL output", layer, tap);
+    return DDIT_ERR_INVALID_ARG;
+  }
+  Layout lo;
+  make_layout(d, shape->flags, &lo);
+  *offset_out = lo.tap_off[layer][tap];
+  *bytes_out = lo.tap_bytes[tap];
+  return DDIT_OK;
+}
+
+int ddit_attn_fwd(ddit_attn_kind kind, const ddit_shape *shape, const void *q, const void *k, const void *v,
+                  int64_t ld_q, int64_t ld_kv, const int32_t *kv_valid_len_host, void *o, int64_t ld_o,
+                  float *lse_or_null, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  if (kind != DDIT_ATTN_SPATIAL && kind != DDIT_ATTN_TEMPORAL && kind != DDIT_ATTN_CROSS) {
+    set_error("unknown attention kind %d", (int)kind); return DDIT_ERR_INVALID_ARG;
+  }
+  if (!q || !k || !v || !o) { set_error("q, k, v and o must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) {
+    set_error("q, k, v and o must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT;
+  }
+  if (ld_q < d.A || ld_kv < d.A || ld_o < d.A) {
+    set_error("leading dimensions (%lld,%lld,%lld) must be at least H*dh=%lld", (long long)ld_q, (long long)ld_kv,
+              (long long)ld_o, (long long)d.A);
+    return DDIT_ERR_INVALID_ARG;
+  }
+  if (ld_q % 8 || ld_kv % 8 || ld_o % 8) { set_error("leading dimensions must be multiples of 8"); return DDIT_ERR_ALIGNMENT; }
+  if (kind == DDIT_ATTN_CROSS) DDIT_TRY(check_valid_len(kv_valid_len_host, d));
+  return run_attention(kind, d, q, k, v, ld_q, ld_kv, kind == DDIT_ATTN_CROSS ? kv_valid_len_host : nullptr, o, ld_o,
+                       lse_or_null, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+int ddit_stdit_block_fwd(const ddit_shape *shape, const ddit_block_weights *weights, const void *x_in,
+                         const void *y, const int32_t *y_valid_len_host, const float *c6, void *x_out,
+                         void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  Layout lo;
+  make_layout(d, shape->flags, &lo);
+  if (!weights || !c6) { set_error("weights and c6 must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (!aligned16(c6)) { set_error("c6 must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT; }
+  DDIT_TRY(check_common(d, lo, x_in, y, x_out, workspace, workspace_bytes));
+  DDIT_TRY(check_valid_len(y_valid_len_host, d));
+  DDIT_TRY(check_layer_weights(weights->spatial, "spatial"));
+  DDIT_TRY(check_layer_weights(weights->temporal, "temporal"));
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
+  float *x = reinterpret_cast<float *>(ws + lo.x);
+  Taps tp{(shape->flags & DDIT_FLAG_TAPS) != 0, ws, &lo, 0, s};
+  DDIT_TRY(launch_cast_bf16_to_f32(x_in, x, d.N * d.D, s));
+  DDIT_TRY(run_layer(DDIT_ATTN_SPATIAL, d, weights->spatial, y, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+  tp.layer = 1;
+  DDIT_TRY(run_layer(DDIT_ATTN_TEMPORAL, d, weights->temporal, y, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+  return launch_cast_f32_to_bf16(x, x_out, d.N * d.D, s);
+}
+
+int ddit_timestep_conditioning(const ddit_shape *shape, const ddit_step_weights *weights,
+                               const float *timesteps_host, const float *temb_or_null, float *c6_out,
+                               float *scratch, void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  if (!weights || !c6_out || !weights->w_ada) { set_error("weights, w_ada and c6_out must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (!temb_or_null) {
+    if (!timesteps_host || !weights->w_t1 || !weights->w_t2 || !scratch) {
+      set_error("timesteps_host, w_t1, w_t2 and scratch are required when no temb is given");
+      return DDIT_ERR_INVALID_ARG;
+    }
+    if (!aligned16(weights->w_t1) || !aligned16(weights->w_t2)) { set_error("w_t1/w_t2 not 16-byte aligned"); return DDIT_ERR_ALIGNMENT; }
+  }
+  if (!aligned16(weights->w_ada)) { set_error("w_ada not 16-byte aligned"); return DDIT_ERR_ALIGNMENT; }
+  CondArgs c;
+  memset(&c, 0, sizeof(c));
+  c.B = (int)d.B; c.D = (int)d.D;
+  if (!temb_or_null)
+    for (int b = 0; b < d.B; ++b) c.t[b] = timesteps_host[b];
+  return launch_timestep_conditioning(c, weights->w_t1, weights->b_t1, weights->w_t2, weights->b_t2, weights->w_ada,
+                                      weights->b_ada, temb_or_null, c6_out, scratch,
+                                      reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+int ddit_denoise_step(const ddit_shape *shape, const ddit_step_weights *weights, const void *x_in,
+                      const void *y, const int32_t *y_valid_len_host, const float *timesteps_host,
+                      const float *temb_or_null, void *x_out, void *workspace, size_t workspace_bytes,
+                      void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  Layout lo;
+  make_layout(d, shape->flags, &lo);
+  if (!weights) { set_error("weights is NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (shape->n_blocks > 0 && !weights->blocks) { set_error("weights->blocks is NULL"); return DDIT_ERR_INVALID_ARG; }
+  DDIT_TRY(check_common(d, lo, x_in, y, x_out, workspace, workspace_bytes));
+  DDIT_TRY(check_valid_len(y_valid_len_host, d));
+  for (int i = 0; i < shape->n_blocks; ++i) {
+    DDIT_TRY(check_layer_weights(weights->blocks[i].spatial, "spatial"));
+    DDIT_TRY(check_layer_weights(weights->blocks[i].temporal, "temporal"));
+  }
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
+  float *x = reinterpret_cast<float *>(ws + lo.x);
+  float *c6 = reinterpret_cast<float *>(ws + lo.c6);
+  DDIT_TRY(ddit_timestep_conditioning(shape, weights, timesteps_host, temb_or_null, c6,
+                                      reinterpret_cast<float *>(ws + lo.cond), hip_stream));
+  Taps tp{(shape->flags & DDIT_FLAG_TAPS) != 0, ws, &lo, 0, s};
+  DDIT_TRY(launch_cast_bf16_to_f32(x_in, x, d.N * d.D, s));
+  for (int i = 0; i < shape->n_blocks; ++i) {
+    tp.layer = 0;
+    DDIT_TRY(run_layer(DDIT_ATTN_SPATIAL, d, weights->blocks[i].spatial, y, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+    tp.layer = 1;
+    DDIT_TRY(run_layer(DDIT_ATTN_TEMPORAL, d, weights->blocks[i].temporal, y, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+  }
+  return launch_cast_f32_to_bf16(x, x_out, d.N * d.D, s);
+}
+
+int ddit_modulated_layernorm_fwd(const float *x, const float *ada_table, const float *c6, int which,
+                                 int64_t N, int64_t tokens_per_sample, int32_t D, float eps, void *out,
+                                 void *hip_stream) {
+  if (!x || !ada_table || !c6 || !out) { set_error("x, ada_table, c6 and out must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (which < 0 || which > 1 || N < 0 || tokens_per_sample < 1 || D < 1 || !(eps > 0.f)) {
+    set_error("modulated_layernorm: which=%d N=%lld tokens_per_sample=%lld D=%d", which, (long long)N,
+              (long long)tokens_per_sample, D);
+    return DDIT_ERR_INVALID_ARG;
+  }
+  if (D % 8) { set_error("D=%d must be a multiple of 8", D); return DDIT_ERR_UNSUPPORTED; }
+  if (!aligned16(x) || !aligned16(ada_table) || !aligned16(c6) || !aligned16(out)) {
+    set_error("pointers must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT;
+  }
+  return launch_modulated_layernorm(x, ada_table, c6, which, N, tokens_per_sample, D, eps, out,
+                                    reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+int ddit_linear_fwd(int epilogue, const void *u, int64_t ld_u, const void *W, const void *bias, int64_t N,
+                    int32_t n, int32_t k, void *out, int64_t ld_out, float *resid, const float *ada_table,
+                    const float *c6, int gate_row, int64_t tokens_per_sample, void *hip_stream) {
+  if (epilogue < 0 || epilogue > 2) { set_error("unknown epilogue %d", epilogue); return DDIT_ERR_INVALID_ARG; }
+  if (!u || !W) { set_error("u and W must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (N < 0 || n < 1 || k < 1 || ld_u < k) { set_error("linear: N=%lld n=%d k=%d ld_u=%lld", (long long)N, n, k, (long long)ld_u); return DDIT_ERR_INVALID_ARG; }
+  if (n % 8 || k % 8 || ld_u % 8) { set_error("n, k and ld_u must be multiples of 8"); return DDIT_ERR_UNSUPPORTED; }
+  if (!aligned16(u) || !aligned16(W) || (bias && !aligned16(bias)) || (out && !aligned16(out)) ||
+      (resid && !aligned16(resid))) {
+    set_error("pointers must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT;
+  }
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.u = u; g.ld_u = ld_u; g.W = W; g.bias = bias; g.N = N; g.n = n; g.k = k;
+  g.tokens_per_sample = tokens_per_sample > 0 ? tokens_per_sample : 1;
+  if (epilogue == DDIT_EPI_RESIDUAL_F32) {
+    if (!resid) { set_error("resid must not be NULL for the residual epilogue"); return DDIT_ERR_INVALID_ARG; }
+    g.resid = resid;
+    if (gate_row >= 0) {
+      if (gate_row > 5 || !ada_table || !c6) { set_error("gate_row=%d needs ada_table and c6, and must be < 6", gate_row); return DDIT_ERR_INVALID_ARG; }
+      if (!aligned16(ada_table) || !aligned16(c6)) { set_error("ada_table and c6 must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT; }
+      g.gate_tab = ada_table + (int64_t)gate_row * n;
+      g.gate_c6 = c6 + (int64_t)gate_row * n;
+      g.gate_c6_stride = 6 * (int64_t)n;
+    }
+    if (out) { if (ld_out < n || ld_out % 8) { set_error("ld_out=%lld invalid", (long long)ld_out); return DDIT_ERR_INVALID_ARG; } }
+  } else {
+    if (!out) { set_error("out must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+    if (ld_out < n || ld_out % 8) { set_error("ld_out=%lld invalid", (long long)ld_out); return DDIT_ERR_INVALID_ARG; }
+  }
+  g.out = out; g.ld_out = ld_out;
+  return launch_gemm(epilogue, g, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,277 @@
+"""Kernel-level parity on the GPU: each stage of the path, called through the C ABI,
+against the matching function of the CPU oracle on the same seeded inputs.
+
+Bar (written out in helpers.assert_parity): per element |gpu-ora| <= 2e-2 (1+|ora|) and
+relative Frobenius error <= 5e-3.  For the attention outputs |O| is small, so the
+Frobenius bound is the binding one."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import ddit_synth as syn
+from helpers import assert_parity, dev_to_f64, rel_fro, to_dev, to_f64
+from oracle import stdit_oracle as ora
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2506_13497_amd as m
+    assert torch.cuda.is_available()
+    return m
+
+
+def _shape(lib, sh, flags=0):
+    return lib.make_shape(sh.B, sh.T, sh.Hp, sh.Wp, sh.D, sh.H, sh.dh, sh.M, sh.Ly, sh.n_blocks, flags)
+
+
+# ----------------------------------------------------------------------------- adaLN + LN
+@pytest.mark.parametrize("N,tps,D", [(256, 256, 256), (37, 19, 1152), (2 * 405, 405, 1152), (9, 9, 4096), (5, 5, 8)])
+def test_modulated_layernorm(lib, N, tps, D):
+    B = (N + tps - 1) // tps
+    rng = np.random.default_rng(N + D)
+    x = (rng.standard_normal((N, D)) * 1.5 + 0.3).astype(np.float32)
+    tab = rng.standard_normal((6, D)).astype(np.float32) * 0.5
+    c6 = rng.standard_normal((B, 6 * D)).astype(np.float32) * 0.5
+    out = torch.empty(N, D, dtype=torch.bfloat16, device="cuda")
+    for which in (0, 1):
+        lib.ddit_modulated_layernorm_fwd(to_dev(x), to_dev(tab), to_dev(c6), which, tps, 1e-6, out)
+        torch.cuda.synchronize()
+        xn = ora.layer_norm(x.astype(np.float64))
+        ref = np.empty((N, D))
+        for n in range(N):
+            m = ora.split_modulation(tab.astype(np.float64), c6[n // tps].astype(np.float64), D)
+            sfx = "msa" if which == 0 else "mlp"
+            ref[n] = ora.modulate(xn[n], m["shift_" + sfx], m["scale_" + sfx])
+        assert_parity(dev_to_f64(out), ref, "modulated LN which=%d" % which)
+
+
+# ----------------------------------------------------------------------------- linear + epilogues
+LIN_CASES = [
+    # N, n, k
+    (256, 768, 256),      # C1 qkv
+    (300, 2304, 1152),    # text k|v projection
+    (1000, 1152, 288),    # k not a multiple of 64 (narrow attention width), ragged N
+    (777, 4608, 1152),    # fc1 shape, ragged token tail, several tiles
+    (515, 1152, 4608),    # fc2 shape
+    (130, 864, 1152),     # n not a multiple of the tile
+    (1, 8, 8),
+]
+
+
+@pytest.mark.parametrize("N,n,k", LIN_CASES)
+@pytest.mark.parametrize("epi", [0, 1, 2])
+def test_linear(lib, N, n, k, epi):
+    u = syn.normal_bits((11, N, n, k), (N, k), 1.0)
+    W = syn.normal_bits((12, N, n, k), (n, k), 1.0 / math.sqrt(k))
+    b = syn.normal_bits((13, N, n, k), (n,), 0.5)
+    lin = ora.linear(to_f64(u), to_f64(W), to_f64(b))
+    du, dW, db = to_dev(u), to_dev(W), to_dev(b)
+    if epi in (0, 1):
+        out = torch.full((N, n), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lib.ddit_linear_fwd(epi, du, k, dW, db, N, n, k, out, n)
+        torch.cuda.synchronize()
+        ref = lin if epi == 0 else ora.gelu_tanh(lin)
+        assert_parity(dev_to_f64(out), ref, "linear epi=%d" % epi)
+    else:
+        tps = max(1, (N + 1) // 2)   # two samples
+        B = (N + tps - 1) // tps
+        rng = np.random.default_rng(5)
+        resid = rng.standard_normal((N, n)).astype(np.float32)
+        tab = rng.standard_normal((6, n)).astype(np.float32)
+        c6 = rng.standard_normal((B, 6 * n)).astype(np.float32)
+        for gate_row in (2, 5, -1):
+            dres = to_dev(resid)
+            out = torch.full((N, n), float("nan"), dtype=torch.bfloat16, device="cuda")
+            lib.ddit_linear_fwd(2, du, k, dW, db, N, n, k, out, n, resid=dres, ada_table=to_dev(tab), c6=to_dev(c6),
+                                gate_row=gate_row, tokens_per_sample=tps)
+            torch.cuda.synchronize()
+            ref = resid.astype(np.float64).copy()
+            for r in range(N):
+                gate = 1.0 if gate_row < 0 else (tab[gate_row] + c6[r // tps].reshape(6, n)[gate_row]).astype(np.float64)
+                ref[r] += gate * lin[r]
+            assert_parity(dev_to_f64(dres), ref, "linear residual gate_row=%d" % gate_row)
+            assert torch.equal(out, dres.to(torch.bfloat16)), "bf16 copy of the stream differs"
+        # without the bf16 copy
+        dres = to_dev(resid)
+        lib.ddit_linear_fwd(2, du, k, dW, None, N, n, k, None, 0, resid=dres)
+        torch.cuda.synchronize()
+        assert_parity(dev_to_f64(dres), resid + ora.linear(to_f64(u), to_f64(W)), "linear residual, no bias/gate/copy")
+
+
+def test_linear_strided_in_out(lib):
+    """u read with a row stride larger than k, out written as a column slice (fused qkv buffer use)."""
+    N, n, k, ld_u, ld_out = 200, 128, 192, 320, 384
+    ubuf = syn.normal_bits((21,), (N, ld_u), 1.0)
+    W = syn.normal_bits((22,), (n, k), 0.1)
+    outbuf = torch.full((N, ld_out), 7.0, dtype=torch.bfloat16, device="cuda")
+    lib.ddit_linear_fwd(0, to_dev(ubuf), ld_u, to_dev(W), None, N, n, k, outbuf, ld_out)
+    torch.cuda.synchronize()
+    ref = ora.linear(to_f64(ubuf)[:, :k], to_f64(W))
+    assert_parity(dev_to_f64(outbuf[:, :n]), ref, "strided linear")
+    assert torch.all(outbuf[:, n:] == 7.0), "wrote outside its column slice"
+
+
+# ----------------------------------------------------------------------------- attention
+def _attn_case(lib, kind, sh, q_scale=1.0, valid=None, seed=0, Lq=None, fused=False):
+    d = syn.make_attn_inputs(kind, sh, 50 + seed, q_scale=q_scale, Lq=Lq)
+    q, k, v = (to_f64(d[n]) for n in "qkv")
+    A = sh.A
+    if kind == "cross":
+        o_ref, lse_ref = ora.cross_attention(q, k, v, valid)
+        kid = lib.DDIT_ATTN_CROSS
+        shape = _shape(lib, syn.small_variant(sh, T=1, Hp=1, Wp=q.shape[1]))
+    else:
+        fn = ora.spatial_attention if kind == "spatial" else ora.temporal_attention
+        o_ref, lse_ref = fn(q, k, v)
+        kid = lib.DDIT_ATTN_SPATIAL if kind == "spatial" else lib.DDIT_ATTN_TEMPORAL
+        shape = _shape(lib, sh)
+    dq, dk, dv = (to_dev(d[n]) for n in "qkv")
+    ld_q = ld_kv = A
+    if fused and kind != "cross":   # q|k|v as column slices of one [tokens, 3A] buffer
+        buf = torch.cat([dq.reshape(-1, A), dk.reshape(-1, A), dv.reshape(-1, A)], dim=1).contiguous()
+        dq, dk, dv = buf[:, :A], buf[:, A:2 * A], buf[:, 2 * A:]
+        ld_q = ld_kv = 3 * A
+    o = torch.full(q.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full(lse_ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+    lib.ddit_attn_fwd(kid, shape, dq, dk, dv, ld_q, ld_kv, None if valid is None else list(valid), o, A, lse)
+    torch.cuda.synchronize()
+    ev, fv = assert_parity(dev_to_f64(o), o_ref, "%s attention O" % kind)
+    assert np.max(np.abs(dev_to_f64(lse) - lse_ref)) < 2e-2, "lse"
+    return ev, fv
+
+
+SELF_SHAPES = [
+    syn.Shape(1, 4, 8, 8, 256, 4, 64, 1024, 16, 1),       # C1: one key tile, dh 64
+    syn.Shape(1, 3, 9, 16, 1152, 2, 72, 4608, 300, 1),    # 144p frame: S=144, three key tiles, ragged
+    syn.Shape(2, 2, 15, 27, 1152, 3, 72, 4608, 300, 1),   # 240p frame: S=405, ragged query and key tails
+    syn.Shape(1, 1, 30, 54, 1152, 1, 72, 4608, 300, 1),   # 480p frame: S=1620
+    syn.Shape(1, 5, 1, 1, 64, 1, 64, 64, 8, 1),           # S=1
+    syn.Shape(1, 2, 13, 5, 128, 2, 64, 64, 8, 1),         # S=65: one key past a tile
+]
+
+
+@pytest.mark.parametrize("sh", SELF_SHAPES, ids=lambda s: "T%dS%dH%ddh%d" % (s.T, s.S, s.H, s.dh))
+@pytest.mark.parametrize("q_scale", [1.0, 4.0])
+def test_spatial_attention(lib, sh, q_scale):
+    _attn_case(lib, "spatial", sh, q_scale=q_scale)
+
+
+def test_spatial_attention_fused_buffer(lib):
+    _attn_case(lib, "spatial", SELF_SHAPES[1], fused=True)
+
+
+TEMPORAL_SHAPES = [
+    syn.Shape(1, 4, 8, 8, 256, 4, 64, 1024, 16, 1),
+    syn.Shape(1, 16, 5, 7, 1152, 16, 72, 4608, 300, 1),
+    syn.Shape(2, 30, 3, 11, 1152, 4, 72, 4608, 300, 1),
+    syn.Shape(1, 1, 4, 4, 1152, 2, 72, 4608, 300, 1),     # T=1: O = V
+    syn.Shape(1, 32, 2, 3, 1152, 1, 72, 4608, 300, 1),
+    syn.Shape(1, 45, 2, 3, 1152, 2, 72, 4608, 300, 1),    # T above the short-sequence kernel's limit
+]
+
+
+@pytest.mark.parametrize("sh", TEMPORAL_SHAPES, ids=lambda s: "T%dS%dH%ddh%d" % (s.T, s.S, s.H, s.dh))
+@pytest.mark.parametrize("q_scale", [1.0, 4.0])
+def test_temporal_attention(lib, sh, q_scale):
+    _attn_case(lib, "temporal", sh, q_scale=q_scale)
+
+
+def test_temporal_attention_fused_buffer(lib):
+    _attn_case(lib, "temporal", TEMPORAL_SHAPES[1], fused=True)
+
+
+@pytest.mark.parametrize("Lq,Ly,H,dh,valid", [
+    (256, 16, 4, 64, None), (256, 16, 4, 64, [5]), (1000, 300, 3, 72, [300]), (1000, 300, 3, 72, [32]),
+    (333, 300, 2, 72, [166]), (70, 300, 2, 72, [1]), (129, 65, 1, 72, [64]),
+])
+def test_cross_attention(lib, Lq, Ly, H, dh, valid):
+    sh = syn.Shape(1, 1, 1, Lq, H * dh, H, dh, 64, Ly, 1)
+    _attn_case(lib, "cross", sh, valid=valid, Lq=Lq)
+    _attn_case(lib, "cross", sh, valid=valid, Lq=Lq, q_scale=4.0, seed=1)
+
+
+def test_cross_attention_batch2_masks(lib):
+    sh = syn.Shape(2, 1, 1, 200, 144, 2, 72, 64, 300, 1)
+    _attn_case(lib, "cross", sh, valid=[45, 290], Lq=200)
+
+
+# ---- closed forms and invariances, on the GPU
+def test_values_of_ones_give_ones(lib):
+    sh = SELF_SHAPES[2]
+    d = syn.make_attn_inputs("spatial", sh, 3)
+    ones = torch.ones((sh.B, sh.T, sh.S, sh.H, sh.dh), dtype=torch.bfloat16, device="cuda")
+    for kid in (lib.DDIT_ATTN_SPATIAL, lib.DDIT_ATTN_TEMPORAL):
+        o = torch.zeros_like(ones)
+        lib.ddit_attn_fwd(kid, _shape(lib, sh), to_dev(d["q"]), to_dev(d["k"]), ones, sh.A, sh.A, None, o, sh.A)
+        torch.cuda.synchronize()
+        assert torch.max(torch.abs(o.float() - 1.0)).item() <= 2 ** -7   # a couple of bf16 ulps at 1.0
+
+
+def test_zero_keys_give_mean_of_values(lib):
+    sh = SELF_SHAPES[1]
+    d = syn.make_attn_inputs("spatial", sh, 4)
+    zk = torch.zeros((sh.B, sh.T, sh.S, sh.H, sh.dh), dtype=torch.bfloat16, device="cuda")
+    o = torch.zeros_like(zk)
+    lse = torch.zeros((sh.B, sh.T, sh.S, sh.H), dtype=torch.float32, device="cuda")
+    lib.ddit_attn_fwd(lib.DDIT_ATTN_SPATIAL, _shape(lib, sh), to_dev(d["q"]), zk, to_dev(d["v"]), sh.A, sh.A, None, o, sh.A, lse)
+    torch.cuda.synchronize()
+    v = to_f64(d["v"])
+    ref = np.broadcast_to(v.mean(axis=2, keepdims=True), v.shape)
+    assert np.max(np.abs(dev_to_f64(o) - ref)) < 3e-3
+    assert np.max(np.abs(dev_to_f64(lse) - math.log(sh.S))) < 1e-3
+
+
+def test_large_common_logit_offset(lib):
+    """Adding one large vector to every key moves each query's logits by a per-row constant far
+    beyond what exp() of a raw logit could take (|offset| up to ~200); the result must stay
+    finite and match the oracle evaluated on the same (bf16-rounded) shifted keys."""
+    sh = SELF_SHAPES[1]
+    d = syn.make_attn_inputs("spatial", sh, 5)
+    u = (np.random.default_rng(0).standard_normal(sh.dh) * 64.0).astype(np.float32)
+    kshift = syn.f32_to_bf16_bits(syn.bits_to_f32(d["k"]) + u)
+    o = torch.zeros((sh.B, sh.T, sh.S, sh.H, sh.dh), dtype=torch.bfloat16, device="cuda")
+    lib.ddit_attn_fwd(lib.DDIT_ATTN_SPATIAL, _shape(lib, sh), to_dev(d["q"]), to_dev(kshift), to_dev(d["v"]),
+                      sh.A, sh.A, None, o, sh.A)
+    torch.cuda.synchronize()
+    ref = ora.spatial_attention(to_f64(d["q"]), to_f64(kshift), to_f64(d["v"]))[0]
+    assert_parity(dev_to_f64(o), ref, "shifted keys")
+
+
+def test_attention_is_deterministic(lib):
+    sh = SELF_SHAPES[2]
+    d = syn.make_attn_inputs("spatial", sh, 6)
+    outs = []
+    for _ in range(2):
+        o = torch.zeros((sh.B, sh.T, sh.S, sh.H, sh.dh), dtype=torch.bfloat16, device="cuda")
+        lib.ddit_attn_fwd(lib.DDIT_ATTN_SPATIAL, _shape(lib, sh), to_dev(d["q"]), to_dev(d["k"]), to_dev(d["v"]), sh.A, sh.A, None, o, sh.A)
+        outs.append(o)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1])
+
+
+# ----------------------------------------------------------------------------- timestep conditioning
+def test_timestep_conditioning(lib):
+    sh = syn.Shape(2, 2, 2, 2, 1152, 16, 72, 4608, 8, 0)
+    sw = syn.make_step_weights(sh, 9, w_std=0.05)
+    dsw = {k: to_dev(v) for k, v in sw.items()}
+    st = lib.step_struct(dsw, [])
+    t = [3.25, 987.5]
+    c6 = torch.empty(sh.B, 6 * sh.D, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(sh.B * (256 + 2 * sh.D), dtype=torch.float32, device="cuda")
+    lib.ddit_timestep_conditioning(_shape(lib, sh), st, t, None, c6, scratch)
+    torch.cuda.synchronize()
+    sw64 = {k: to_f64(v) for k, v in sw.items()}
+    ref = ora.conditioning(ora.timestep_embedding(np.array(t), sw64), sw64)
+    assert rel_fro(dev_to_f64(c6), ref) < 1e-4
+    # the sinusoidal features themselves (first 256 floats per sample of the scratch)
+    feat = dev_to_f64(scratch[:sh.B * 256].reshape(sh.B, 256))
+    assert np.max(np.abs(feat - ora.timestep_features(np.array(t)))) < 1e-6
+    # a given temb bypasses the embedder
+    temb = syn.make_temb(sh, 9)
+    lib.ddit_timestep_conditioning(_shape(lib, sh), st, None, to_dev(temb), c6, None)
+    torch.cuda.synchronize()
+    assert rel_fro(dev_to_f64(c6), ora.conditioning(temb.astype(np.float64), sw64)) < 1e-4
