@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the STDiT denoising step on one MI355X.
+
+A step = one full pass of the hot path (timestep conditioning + 28 blocks = 56 layers) over
+one synthetic 480p-shaped batch (B=1, T=30, 30x54 tokens per frame, L=48600, hidden 1152,
+16 heads x 72, MLP 4608, 300 text tokens with a seeded padding mask).  Inputs and weights
+are resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4|C5|C3|C2] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
+
+WORKLOAD_NAMES = {"C2": "144p", "C3": "240p-b2", "C4": "480p", "C5": "720p-share-4of16-heads"}
+
+
+def step_flops(sh, valid):
+    """Algorithmic FLOPs of one step: 2*m*n*k per linear, 4*Lq*Lk*dh per attention head (head dim 72,
+    not the padded width; cross-attention counted at the actual valid text length)."""
+    N, D, A, M, S, T, L, Ly = sh.N, sh.D, sh.A, sh.M, sh.S, sh.T, sh.L, sh.Ly
+    lin = lambda rows, n, k: 2.0 * rows * n * k
+    per_layer_common = lin(N, 3 * A, D) + lin(N, D, A) + lin(N, A, D) + lin(sh.B * Ly, 2 * A, D) + lin(N, D, A) \
+        + lin(N, M, D) + lin(N, D, M)
+    cross = sum(4.0 * L * int(v) * A for v in valid)
+    spatial = 4.0 * N * S * A
+    temporal = 4.0 * N * T * A
+    per_block = 2 * per_layer_common + 2 * cross + spatial + temporal
+    return {"step": sh.n_blocks * per_block, "gemm_layer": per_layer_common, "spatial": spatial,
+            "temporal": temporal, "cross": cross, "fc1": lin(N, M, D)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C4", choices=sorted(WORKLOAD_NAMES))
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-stages", action="store_true", help="skip the per-kernel timings")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one rank's share of the step); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import ddit_synth as syn
+    import paper_2506_13497_amd as m   # raises if the HIP library is not built
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = syn.CONFIGS[args.workload]
+    sh, base = cfg["shape"], cfg["base"]
+
+    t0 = time.time()
+    # Weights are drawn on the device (seeded torch generator, same N(0, 0.02^2) distribution and
+    # shapes as ddit_synth, which the parity tests use): 1.2 G numpy draws would take minutes.
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1000 + base)
+
+    def draw(shape_, std, dtype=torch.bfloat16):
+        t = torch.randn(shape_, generator=gen, device="cuda", dtype=torch.float32) * std
+        return t.to(torch.bfloat16).to(dtype)   # fp32 tensors hold bf16-representable values
+
+    sw = {k: draw(s_, 0.02) for k, s_ in syn.step_shapes(sh).items()}
+    blocks = []
+    for i in range(sh.n_blocks):
+        blocks.append({kind: {n: draw(s_, 0.02, torch.float32 if n == "ada_table" else torch.bfloat16)
+                              for n, s_ in syn.layer_shapes(sh).items()} for kind in ("spatial", "temporal")})
+    x_in, y = draw((sh.B, sh.T, sh.S, sh.D), 1.0), draw((sh.B, sh.Ly, sh.D), 1.0)
+    valid = [int(v) for v in syn.make_valid_len(sh, base, cfg["valid"])]
+    tsteps = [float(t) for t in syn.make_timesteps(sh, base, cfg["t"])]
+    shape = m.make_shape(sh.B, sh.T, sh.Hp, sh.Wp, sh.D, sh.H, sh.dh, sh.M, sh.Ly, sh.n_blocks)
+    ws = m.alloc_workspace(shape)
+    st = m.step_struct(sw, blocks)
+    x_out = torch.empty_like(x_in)
+    torch.cuda.synchronize()
+    print("[bench] %s: inputs+weights resident after %.1fs (workspace %.2f GB)" %
+          (args.workload, time.time() - t0, ws.numel() / 1e9), file=sys.stderr, flush=True)
+
+    def one_step():
+        m.ddit_denoise_step(shape, st, x_in, y, valid, tsteps, None, x_out, ws)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t1) * 1e3 / max(args.steps, 1)
+    fl = step_flops(sh, valid)
+    step_tflops = fl["step"] / (ms_per_step * 1e-3) / 1e12
+    print("[bench] step %.2f ms, %.1f TFLOP/s algorithmic" % (ms_per_step, step_tflops), file=sys.stderr, flush=True)
+
+    # ---- per-kernel timings with HIP events on the stream the kernels run on
+    def time_call(fn, reps):
+        fn(); fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps   # ms
+
+    stages, roofline = {}, None
+    if not args.no_stages:
+        N, D, A, M = sh.N, sh.D, sh.A, sh.M
+        lw = blocks[0]["spatial"]
+        xh = torch.randn(N, D, device="cuda").to(torch.bfloat16)
+        h = torch.empty(N, M, dtype=torch.bfloat16, device="cuda")
+        reps = max(args.steps, 5)
+        ms = time_call(lambda: m.ddit_linear_fwd(m.DDIT_EPI_GELU_BF16, xh, D, lw["w_fc1"], lw["b_fc1"], N, M, D, h, M), reps)
+        tf = fl["fc1"] / (ms * 1e-3) / 1e12
+        roofline = {"kernel": "k_gemm_bf16<256,192,GELU> (MLP fc1, %dx%dx%d)" % (N, M, D), "bound": "mfma",
+                    "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tf / PEAK_BF16_TFLOPS, 4), "ms_per_launch": round(ms, 4), "traffic": None}
+        stages["fc1_gelu"] = {"ms": round(ms, 4), "tflops": round(tf, 1), "frac_mfma": round(tf / PEAK_BF16_TFLOPS, 4)}
+        qkv = torch.randn(N, 3 * A, device="cuda").to(torch.bfloat16)
+        o = torch.empty(N, A, dtype=torch.bfloat16, device="cuda")
+        for name, kind, flops in (("spatial_attention", m.DDIT_ATTN_SPATIAL, fl["spatial"]),
+                                  ("temporal_attention", m.DDIT_ATTN_TEMPORAL, fl["temporal"])):
+            ms = time_call(lambda: m.ddit_attn_fwd(kind, shape, qkv[:, :A], qkv[:, A:2 * A], qkv[:, 2 * A:], 3 * A, 3 * A,
+                                                   None, o, A), reps)
+            tf = flops / (ms * 1e-3) / 1e12
+            gbs = 8.0 * N * A / (ms * 1e-3) / 1e9     # q,k,v read + o written once, bf16
+            stages[name] = {"ms": round(ms, 4), "tflops": round(tf, 1), "frac_mfma": round(tf / PEAK_BF16_TFLOPS, 4),
+                            "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+        kvc = torch.randn(sh.B * sh.Ly, 2 * A, device="cuda").to(torch.bfloat16)
+        ms = time_call(lambda: m.ddit_attn_fwd(m.DDIT_ATTN_CROSS, shape, qkv[:, :A], kvc[:, :A], kvc[:, A:], 3 * A, 2 * A,
+                                               valid, o, A), reps)
+        tf = fl["cross"] / (ms * 1e-3) / 1e12
+        stages["cross_attention"] = {"ms": round(ms, 4), "tflops": round(tf, 1), "frac_mfma": round(tf / PEAK_BF16_TFLOPS, 4),
+                                     "valid_len": valid}
+        x32 = torch.randn(N, D, device="cuda")
+        c6 = torch.randn(sh.B, 6 * D, device="cuda")
+        ms = time_call(lambda: m.ddit_modulated_layernorm_fwd(x32, lw["ada_table"], c6, 0, sh.L, 1e-6, xh), reps)
+        gbs = 6.0 * N * D / (ms * 1e-3) / 1e9
+        stages["modulated_layernorm"] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+        del xh, h, qkv, o, kvc, x32
+        print("[bench] stages: %s" % json.dumps(stages), file=sys.stderr, flush=True)
+
+    # ---- CPU oracle on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu:
+        from oracle import stdit_oracle as ora
+        f64 = lambda a: syn.bits_to_f64(a) if a.dtype == np.uint16 else a.astype(np.float64)
+        Ts = 1                # one frame of the same frame size: every stage is linear in frames
+        shs = syn.small_variant(sh, T=Ts)
+        wl = {k: v.double().cpu().numpy() for k, v in blocks[0]["spatial"].items()}
+        xs = x_in[:, :Ts].double().cpu().numpy()
+        ys = y.double().cpu().numpy()
+        c6s = f64(syn.make_c6(sh, base, 0.5))
+        tc = time.perf_counter()
+        ora.layer_fwd("spatial", xs, ys, np.array(valid), c6s, wl, sh.H, sh.dh)
+        dt = time.perf_counter() - tc
+        layers = 2 * sh.n_blocks
+        est_ms = dt * (sh.T / Ts) * layers * 1e3
+        try:
+            from threadpoolctl import threadpool_info
+            nthr = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            nthr = os.cpu_count()
+        cpu = {"value": round(est_ms, 1), "unit": "ms", "cores": int(nthr), "kind": "oracle",
+               "sample": "one spatial layer of the fp64 numpy oracle on %d of %d frames (%d tokens), %.1f s; scaled x%.1f "
+                         "frames x%d layers to a full step" % (Ts, sh.T, shs.N, dt, sh.T / Ts, layers)}
+
+    out = {
+        "metric": "DiT denoise-step latency (ms) at 480p-shaped latents; attention TFLOP/s in 'stages'",
+        "value": round(ms_per_step, 3), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s (%s): B=%d T=%d S=%d L=%d D=%d heads=%dx%d M=%d Ly=%d valid=%s blocks=%d" %
+                   (args.workload, WORKLOAD_NAMES[args.workload], sh.B, sh.T, sh.S, sh.L, sh.D, sh.H, sh.dh, sh.M, sh.Ly,
+                    valid, sh.n_blocks)},
+        "step_tflops": round(step_tflops, 1), "step_frac_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
+        "step_algorithmic_tflop": round(fl["step"] / 1e12, 2),
+        "roofline": roofline, "stages": stages, "cpu_baseline": cpu,
+        "paper_context": "paper reports only 'several seconds to tens of seconds' of DiT time per 30-step request on "
+                         "H800 at 144p-360p (section 6.3); no per-step figure to compare with",
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
