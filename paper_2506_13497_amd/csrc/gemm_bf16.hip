@@ -9,19 +9,28 @@
 // BN out-features) and walks k in steps of 64.  The wavefronts form a 2x2 grid; each
 // owns (BM/2) x (BN/2), i.e. (BM/64)*(BN/64) MFMA tiles of 32x32 with fp32 accumulators
 // in registers.  The MFMA is issued with W as its first operand and u as its second, so
-// a lane ends up holding, for one token, 4 consecutive out-features per accumulator
-// group: the epilogue reads/writes 8-byte (bf16) or 16-byte (fp32) pieces per lane.
+// a lane ends up holding, for one token, 4 consecutive out-features per accumulator group.
 // LDS holds two stages of (BM + BN) rows x 128 B.  A row's eight 16-byte chunks are
 // stored at chunk position c ^ (row & 7): the ds_read_b128 of 8 consecutive rows at the
-// same k then touches all 32 banks once.  Global loads for step i+2 are in flight while
-// step i is multiplied; one barrier per step.
+// same k then touches all 32 banks once.
 //
-// Workgroup -> tile map.  Workgroups are dealt round-robin to the 8 XCDs, each with its
-// own L2, so ids are re-numbered to give every XCD a contiguous run of tiles, ordered
-// with the out-feature tile fastest: the CUs of one XCD share a token panel of u.
+// Pipeline.  A k-step is four sub-steps of 16.  The fragments of sub-step s+1 are read
+// from LDS while the MFMAs of sub-step s run (register double buffer); the LDS writes of
+// k-step i+1 and the global loads of k-step i+2 are slotted between the MFMAs of
+// sub-steps 0 and 1; the last sub-step prefetches the first fragments of the next stage.
+// One barrier per k-step.  The issue order inside a sub-step is pinned with
+// sched_group_barrier, since with one wavefront per SIMD nothing else hides LDS latency.
 //
-// Epilogues: bf16 store; GELU(tanh form) + bf16 store; gated residual update of the
-// fp32 stream (x += gate_b * (acc + bias)), optionally also storing bf16(x).
+// Persistent workgroups.  The grid is one workgroup per CU; each loops over output
+// tiles.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so in
+// every round the 32 workgroups of an XCD take 32 consecutive tiles, out-feature tile
+// fastest: they share a token panel of u.  The next tile's first global loads are issued
+// before the epilogue, and the epilogue's stores drain while the next tile is multiplied.
+//
+// Epilogue.  The accumulators are staged through LDS (free once the k loop is done) so
+// that global memory is written in whole-row pieces, 16 bytes per lane, instead of 8-byte
+// pieces scattered over 32 rows: bf16 store; GELU(tanh form) + bf16 store; gated residual
+// update of the fp32 stream (x += gate_b * (acc + bias)), optionally also storing bf16(x).
 #include "ddit_common.hpp"
 
 namespace {
@@ -39,7 +48,7 @@ struct GemmParams {
   const float *gate_tab;
   const float *gate_c6; int64_t gate_c6_stride;
   int64_t tokens_per_sample;
-  int tiles_n; int64_t total_tiles;
+  int tiles_n; int total_tiles; int rounds;
 };
 
 __device__ __forceinline__ float gelu_tanh_f(float u) {
@@ -50,173 +59,398 @@ __device__ __forceinline__ float gelu_tanh_f(float u) {
   return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z2));
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for the
+// epilogue's global stores of the previous tile to be acknowledged, which is exactly the
+// overlap the persistent loop is after; nothing in this kernel communicates through global
+// memory inside a workgroup.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// scheduling-group masks of __builtin_amdgcn_sched_group_barrier
+#define SG_MFMA 0x008
+#define SG_VMEM_RD 0x020
+#define SG_DS_RD 0x100
+#define SG_DS_WR 0x200
+
+// Issue order for one sub-step: NM MFMAs with NS instructions of class OTHER spread between them.
+template <int OTHER, int I, int NM, int NS>
+__device__ __forceinline__ void sched_interleave() {
+  if constexpr (I < NM) {
+    __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+    constexpr int cnt = (I < NS % NM ? 1 : 0) + NS / NM;
+    if constexpr (cnt > 0) __builtin_amdgcn_sched_group_barrier(OTHER, cnt, 0);
+    sched_interleave<OTHER, I + 1, NM, NS>();
+  }
+}
+
+template <int BM, int BN>
+struct GemmCfg {
+  static constexpr int STAGE = (BM + BN) * ROW_BYTES;
+  static constexpr int PITCH_BF16 = BN * 2 + 16;             // epilogue staging row pitches: +16 B keeps the
+  static constexpr int PITCH_F32 = BN * 4 + 16;              // 8 lanes of a 16-byte access on distinct banks
+  static constexpr int EPI_BF16_BYTES = BM * PITCH_BF16;
+  static constexpr int EPI_F32_BYTES = (BM / 2) * PITCH_F32;  // fp32 staging goes in two halves of BM/2 rows
+  static constexpr int MAIN_BYTES = 2 * STAGE;
+  static constexpr int SMEM = MAIN_BYTES > EPI_BF16_BYTES ? (MAIN_BYTES > EPI_F32_BYTES ? MAIN_BYTES : EPI_F32_BYTES)
+                                                          : (EPI_BF16_BYTES > EPI_F32_BYTES ? EPI_BF16_BYTES : EPI_F32_BYTES);
+};
+
 template <int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
+  using C = GemmCfg<BM, BN>;
   constexpr int TM = BM / 64;  // 32-token MFMA tiles per wave
   constexpr int TN = BN / 64;  // 32-feature MFMA tiles per wave
   constexpr int U_CH = BM * 8 / 256;  // 16-byte chunks per thread per stage
   constexpr int W_CH = BN * 8 / 256;
-  constexpr int STAGE = (BM + BN) * ROW_BYTES;
+  constexpr int STAGE = C::STAGE;
+  constexpr int NFRAG = TM + TN;
+  constexpr int NMFMA = TM * TN;
+  constexpr int NST = U_CH + W_CH;  // staging chunks per thread = ds_writes = global loads per k-step
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-  // ---- XCD-aware tile id
-  const int64_t pid = blockIdx.x;
-  const int64_t q8 = p.total_tiles >> 3, r8 = p.total_tiles & 7;
-  const int64_t xcd = pid & 7, loc = pid >> 3;
-  const int64_t tile = xcd * q8 + (xcd < r8 ? xcd : r8) + loc;
-  const int64_t tile_m = tile / p.tiles_n;
-  const int tile_n = (int)(tile - tile_m * p.tiles_n);
-  const int64_t row0 = tile_m * BM;
-  const int col0 = tile_n * BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, lh = lane >> 5;
+  const int ld_r = tid >> 3, ld_c = tid & 7;  // staging: row ld_r (+32 per extra chunk), 16-byte chunk ld_c
+  const bf16_t *u_base = p.u + ld_c * 8;
+  const bf16_t *w_base = p.W + ld_c * 8;
+  // LDS byte offset of this thread's staging chunk (row ld_r + 32 i keeps (row & 7) == (ld_r & 7))
+  const int st_off = ld_r * ROW_BYTES + ((ld_c ^ (ld_r & 7)) << 4);
+  // fragment read offsets: row (tile*32 + l32), chunk (2 kk + lh) swizzled by (row & 7) == (l32 & 7)
+  const int frag_u = (wm * (BM / 2) + l32) * ROW_BYTES;
+  const int frag_w = BM * ROW_BYTES + (wn * (BN / 2) + l32) * ROW_BYTES;
+  int coff[BK / 16];
+#pragma unroll
+  for (int kk = 0; kk < BK / 16; ++kk) coff[kk] = ((kk * 2 + lh) ^ (l32 & 7)) << 4;
+  const int nk = (p.k + BK - 1) / BK;
+  const int n_steady = (p.k / BK) - 2;  // k-steps kt with kt+2 a full step
 
-  // ---- global -> register staging: chunk idx -> (row r, 16-byte chunk c)
-  const int ld_r = tid >> 3, ld_c = tid & 7;  // + 32 rows per extra chunk
-  const bf16_t *u_ptr[U_CH];
-  const bf16_t *w_ptr[W_CH];
-#pragma unroll
-  for (int i = 0; i < U_CH; ++i) {
-    int64_t r = row0 + ld_r + 32 * i;
-    if (r > p.N - 1) r = p.N - 1;  // overhanging rows re-read the last token; never stored
-    u_ptr[i] = p.u + r * p.ld_u + ld_c * 8;
-  }
-#pragma unroll
-  for (int i = 0; i < W_CH; ++i) {
-    int r = col0 + ld_r + 32 * i;
-    if (r > p.n - 1) r = p.n - 1;
-    w_ptr[i] = p.W + (int64_t)r * p.k + ld_c * 8;
-  }
+  // tile of this workgroup in round r: the 32 workgroups of an XCD take 32 consecutive tiles
+  const int G = gridDim.x;
+  const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
+  const int per_xcd = (G + 7) >> 3;
+  auto tile_of = [&](int r) -> int {
+    const int t = r * G + xcd * per_xcd + loc;
+    // G is a multiple of 8 whenever there is more than one round, so this is a bijection
+    return t;
+  };
+
+  int u_off[U_CH];   // element offsets; the host checks that they fit 31 bits
+  int w_off[W_CH];
   uint4 u_reg[U_CH], w_reg[W_CH];
-  const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
-
-  auto g_load = [&](int k0) {
-    const bool ok = (k0 + ld_c * 8) < p.k;  // k tail: zero-fill both operands
-#pragma unroll
-    for (int i = 0; i < U_CH; ++i) u_reg[i] = ok ? *reinterpret_cast<const uint4 *>(u_ptr[i] + k0) : zero4;
-#pragma unroll
-    for (int i = 0; i < W_CH; ++i) w_reg[i] = ok ? *reinterpret_cast<const uint4 *>(w_ptr[i] + k0) : zero4;
-  };
-  auto s_store = [&](int stage) {
-    unsigned char *su = smem + stage * STAGE;
-    unsigned char *sw = su + BM * ROW_BYTES;
-#pragma unroll
-    for (int i = 0; i < U_CH; ++i) {
-      const int r = ld_r + 32 * i;
-      *reinterpret_cast<uint4 *>(su + r * ROW_BYTES + ((ld_c ^ (r & 7)) << 4)) = u_reg[i];
-    }
-#pragma unroll
-    for (int i = 0; i < W_CH; ++i) {
-      const int r = ld_r + 32 * i;
-      *reinterpret_cast<uint4 *>(sw + r * ROW_BYTES + ((ld_c ^ (r & 7)) << 4)) = w_reg[i];
-    }
-  };
-
-  floatx16 acc[TN][TM];
+  // bias of this lane's out-features; the accumulators START from it (so no epilogue load)
+  bf16x4 bias_r[TN][4];
 #pragma unroll
   for (int a = 0; a < TN; ++a)
 #pragma unroll
-    for (int b = 0; b < TM; ++b)
+    for (int g = 0; g < 4; ++g)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+      for (int e = 0; e < 4; ++e) bias_r[a][g][e] = (bf16_t)0.f;
 
-  const int nk = (p.k + BK - 1) / BK;
-  g_load(0);
-  s_store(0);
-  if (nk > 1) g_load(BK);
-  __syncthreads();
+#define GEMM_SET_TILE(TILE)                                                                        \
+  do {                                                                                             \
+    const int tile_m_ = (TILE) / p.tiles_n;                                                        \
+    const int tile_n_ = (TILE) - tile_m_ * p.tiles_n;                                              \
+    row0 = (int64_t)tile_m_ * BM;                                                                  \
+    col0 = tile_n_ * BN;                                                                           \
+    _Pragma("unroll") for (int i = 0; i < U_CH; ++i) {                                             \
+      int64_t r_ = row0 + ld_r + 32 * i;                                                           \
+      if (r_ > p.N - 1) r_ = p.N - 1; /* overhanging rows re-read the last row; never stored */    \
+      u_off[i] = (int)(r_ * p.ld_u);                                                               \
+    }                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < W_CH; ++i) {                                             \
+      int r_ = col0 + ld_r + 32 * i;                                                               \
+      if (r_ > p.n - 1) r_ = p.n - 1;                                                              \
+      w_off[i] = r_ * p.k;                                                                         \
+    }                                                                                              \
+  } while (0)
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) s_store(cur ^ 1);         // registers hold step kt+1
-    if (kt + 2 < nk) g_load((kt + 2) * BK);    // in flight during the multiply below
-    const unsigned char *su = smem + cur * STAGE + (wm * (BM / 2)) * ROW_BYTES;
-    const unsigned char *sw = smem + cur * STAGE + BM * ROW_BYTES + (wn * (BN / 2)) * ROW_BYTES;
+#define GEMM_BIAS_LOAD()                                                                           \
+  do {                                                                                             \
+    if (p.bias) {                                                                                  \
+      _Pragma("unroll") for (int a = 0; a < TN; ++a)                                               \
+          _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                          \
+        int f_ = col0 + wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;                                   \
+        if (f_ > p.n - 4) f_ = p.n - 4; /* overhanging features: a valid address, never stored */  \
+        bias_r[a][g] = *reinterpret_cast<const bf16x4 *>(p.bias + f_);                             \
+      }                                                                                            \
+    }                                                                                              \
+  } while (0)
+
+#define GEMM_G_LOAD(K0)                                                                            \
+  do {                                                                                             \
+    const int k0_ = (K0);                                                                          \
+    if (k0_ + ld_c * 8 < p.k) {                                                                    \
+      _Pragma("unroll") for (int i = 0; i < U_CH; ++i)                                             \
+          u_reg[i] = *reinterpret_cast<const uint4 *>(u_base + u_off[i] + k0_);                    \
+      _Pragma("unroll") for (int i = 0; i < W_CH; ++i)                                             \
+          w_reg[i] = *reinterpret_cast<const uint4 *>(w_base + w_off[i] + k0_);                    \
+    } else { /* k tail: zero-fill both operands */                                                 \
+      _Pragma("unroll") for (int i = 0; i < U_CH; ++i) u_reg[i] = make_uint4(0u, 0u, 0u, 0u);      \
+      _Pragma("unroll") for (int i = 0; i < W_CH; ++i) w_reg[i] = make_uint4(0u, 0u, 0u, 0u);      \
+    }                                                                                              \
+  } while (0)
+
+#define GEMM_G_LOAD_FULL(K0)                                                                       \
+  do {                                                                                             \
+    const int k0_ = (K0);                                                                          \
+    _Pragma("unroll") for (int i = 0; i < U_CH; ++i)                                               \
+        u_reg[i] = *reinterpret_cast<const uint4 *>(u_base + u_off[i] + k0_);                      \
+    _Pragma("unroll") for (int i = 0; i < W_CH; ++i)                                               \
+        w_reg[i] = *reinterpret_cast<const uint4 *>(w_base + w_off[i] + k0_);                      \
+  } while (0)
+
+#define GEMM_S_STORE(STAGE_IDX)                                                                    \
+  do {                                                                                             \
+    unsigned char *su_ = smem + (STAGE_IDX) * STAGE + st_off;                                      \
+    unsigned char *sw_ = su_ + BM * ROW_BYTES;                                                     \
+    _Pragma("unroll") for (int i = 0; i < U_CH; ++i)                                               \
+        *reinterpret_cast<uint4 *>(su_ + i * 32 * ROW_BYTES) = u_reg[i];                           \
+    _Pragma("unroll") for (int i = 0; i < W_CH; ++i)                                               \
+        *reinterpret_cast<uint4 *>(sw_ + i * 32 * ROW_BYTES) = w_reg[i];                           \
+  } while (0)
+
+#define GEMM_READ_FRAGS(BUF, STAGE_IDX, KK)                                                        \
+  do {                                                                                             \
+    const unsigned char *sb_ = smem + (STAGE_IDX) * STAGE + coff[KK];                              \
+    _Pragma("unroll") for (int b = 0; b < TM; ++b)                                                 \
+        uf[BUF][b] = *reinterpret_cast<const bf16x8 *>(sb_ + frag_u + b * 32 * ROW_BYTES);         \
+    _Pragma("unroll") for (int a = 0; a < TN; ++a)                                                 \
+        wf[BUF][a] = *reinterpret_cast<const bf16x8 *>(sb_ + frag_w + a * 32 * ROW_BYTES);         \
+  } while (0)
+
+#define GEMM_MFMAS(BUF)                                                                            \
+  do {                                                                                             \
+    _Pragma("unroll") for (int a = 0; a < TN; ++a)                                                 \
+        _Pragma("unroll") for (int b = 0; b < TM; ++b)                                             \
+            acc[a][b] = mfma32(wf[BUF][a], uf[BUF][b], acc[a][b]);                                 \
+  } while (0)
+
+  int64_t row0 = 0;
+  int col0 = 0;
+  int tile = tile_of(0);
+  if (tile >= p.total_tiles) return;
+  GEMM_SET_TILE(tile);
+  GEMM_BIAS_LOAD();
+  GEMM_G_LOAD(0);
+
+  for (int round = 0;; ++round) {
+    // ---- prologue: the registers hold k-step 0 of this tile
+    const int64_t my_row0 = row0;
+    const int my_col0 = col0;
+    GEMM_S_STORE(0);
+    if (nk > 1) GEMM_G_LOAD(BK);
+    floatx16 acc[TN][TM];
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const int c = kk * 2 + lh;
-      bf16x8 uf[TM], wf[TN];
+    for (int a = 0; a < TN; ++a)
 #pragma unroll
-      for (int b = 0; b < TM; ++b) {
-        const int r = b * 32 + l32;
-        uf[b] = *reinterpret_cast<const bf16x8 *>(su + r * ROW_BYTES + ((c ^ (r & 7)) << 4));
-      }
+      for (int b = 0; b < TM; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[a][b][e] = (float)bias_r[a][e >> 2][e & 3];
+    lds_barrier();
+
+    bf16x8 uf[2][TM], wf[2][TN];
+    GEMM_READ_FRAGS(0, 0, 0);
+    int kt = 0;
+    // ---- steady state: k-steps kt+1 and kt+2 exist and kt+2 is a full step; no branches inside,
+    // so each sub-step is one scheduling region with an explicit issue order
+    for (; kt < n_steady; ++kt) {
+      const int cur = kt & 1;
+      // sub-step 0: stage k-step kt+1 into the other buffer
+      GEMM_READ_FRAGS(1, cur, 1);
+      GEMM_S_STORE(cur ^ 1);
+      GEMM_MFMAS(0);
+      __builtin_amdgcn_sched_group_barrier(SG_DS_RD, NFRAG, 0);
+      sched_interleave<SG_DS_WR, 0, NMFMA, NST>();
+      __builtin_amdgcn_sched_barrier(0);
+      // sub-step 1: issue the global loads of k-step kt+2
+      GEMM_READ_FRAGS(0, cur, 2);
+      GEMM_G_LOAD_FULL((kt + 2) * BK);
+      GEMM_MFMAS(1);
+      __builtin_amdgcn_sched_group_barrier(SG_DS_RD, NFRAG, 0);
+      sched_interleave<SG_VMEM_RD, 0, NMFMA, NST>();
+      __builtin_amdgcn_sched_barrier(0);
+      // sub-step 2
+      GEMM_READ_FRAGS(1, cur, 3);
+      __builtin_amdgcn_sched_barrier(0);
+      GEMM_MFMAS(0);
+      __builtin_amdgcn_sched_barrier(0);
+      // Past this barrier every wave's last read of the current stage has returned and its
+      // writes of the next stage are done: the next stage may be read, and the following
+      // k-step may overwrite the current one.
+      lds_barrier();
+      // sub-step 3: first fragments of the next stage
+      GEMM_READ_FRAGS(0, cur ^ 1, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      GEMM_MFMAS(1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // ---- the last k-steps (and the k tail, zero-filled)
+    for (; kt < nk; ++kt) {
+      const int cur = kt & 1;
+      const bool has_next = kt + 1 < nk;
+      if (has_next) GEMM_S_STORE(cur ^ 1);
+      GEMM_READ_FRAGS(1, cur, 1);
+      GEMM_MFMAS(0);
+      if (kt + 2 < nk) GEMM_G_LOAD((kt + 2) * BK);
+      GEMM_READ_FRAGS(0, cur, 2);
+      GEMM_MFMAS(1);
+      GEMM_READ_FRAGS(1, cur, 3);
+      GEMM_MFMAS(0);
+      lds_barrier();
+      if (has_next) GEMM_READ_FRAGS(0, cur ^ 1, 0);
+      GEMM_MFMAS(1);
+    }
+    // every wave is past the last barrier of the k loop: no LDS read of the stages is pending
+
+    // ---- epilogue.  acc[a][b][4g+e] = C[token tb + l32][feature fb + 8g + 4 lh + e]
+    // ---- next tile: start its first global loads now, they land during the epilogue
+    const int next_tile = (round + 1 < p.rounds) ? tile_of(round + 1) : p.total_tiles;
+    const bool more = next_tile < p.total_tiles;
+    if (more) {
+      GEMM_SET_TILE(next_tile);
+      GEMM_BIAS_LOAD();
+      GEMM_G_LOAD(0);
+    }
+
+    if constexpr (EPI != 2) {
+      // bias (+ GELU), round to bf16, stage the whole BM x BN tile, then store whole rows
 #pragma unroll
       for (int a = 0; a < TN; ++a) {
-        const int r = a * 32 + l32;
-        wf[a] = *reinterpret_cast<const bf16x8 *>(sw + r * ROW_BYTES + ((c ^ (r & 7)) << 4));
-      }
 #pragma unroll
-      for (int a = 0; a < TN; ++a)
+        for (int g = 0; g < 4; ++g) {
+          const int fl = wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;   // feature inside the tile
 #pragma unroll
-        for (int b = 0; b < TM; ++b) acc[a][b] = mfma32(wf[a], uf[b], acc[a][b]);
-    }
-    __syncthreads();
-  }
-
-  // ---- epilogue: acc[a][b][4g+e] = C[token = tb + l32][feature = fb + 8g + 4 lh + e]
-#pragma unroll
-  for (int b = 0; b < TM; ++b) {
-    const int64_t tok = row0 + wm * (BM / 2) + b * 32 + l32;
-    if (tok >= p.N) continue;
-    int64_t sample = 0;
-    if (EPI == 2 && p.gate_c6) sample = tok / p.tokens_per_sample;
-#pragma unroll
-    for (int a = 0; a < TN; ++a) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int f = col0 + wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;
-        if (f >= p.n) continue;
-        float v0 = acc[a][b][4 * g + 0], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
-              v3 = acc[a][b][4 * g + 3];
-        if (p.bias) {
-          const bf16x4 bb = *reinterpret_cast<const bf16x4 *>(p.bias + f);
-          v0 += (float)bb[0]; v1 += (float)bb[1]; v2 += (float)bb[2]; v3 += (float)bb[3];
-        }
-        if (EPI == 1) {
-          v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
-        }
-        if (EPI == 2) {
-          if (p.gate_tab) {
-            float4 gt = *reinterpret_cast<const float4 *>(p.gate_tab + f);
-            if (p.gate_c6) {
-              const float4 gc = *reinterpret_cast<const float4 *>(p.gate_c6 + sample * p.gate_c6_stride + f);
-              gt.x += gc.x; gt.y += gc.y; gt.z += gc.z; gt.w += gc.w;
+          for (int b = 0; b < TM; ++b) {
+            float v0 = acc[a][b][4 * g + 0], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
+                  v3 = acc[a][b][4 * g + 3];
+            if (EPI == 1) {
+              v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
             }
-            v0 *= gt.x; v1 *= gt.y; v2 *= gt.z; v3 *= gt.w;
+            bf16x4 o;
+            o[0] = (bf16_t)v0; o[1] = (bf16_t)v1; o[2] = (bf16_t)v2; o[3] = (bf16_t)v3;
+            const int rl = wm * (BM / 2) + b * 32 + l32;             // token inside the tile
+            *reinterpret_cast<bf16x4 *>(smem + rl * C::PITCH_BF16 + fl * 2) = o;
           }
-          float4 *rp = reinterpret_cast<float4 *>(p.resid + tok * (int64_t)p.n + f);
-          float4 r = *rp;
-          r.x += v0; r.y += v1; r.z += v2; r.w += v3;
-          *rp = r;
-          v0 = r.x; v1 = r.y; v2 = r.z; v3 = r.w;
-          if (!p.out) continue;
         }
-        bf16x4 o;
-        o[0] = (bf16_t)v0; o[1] = (bf16_t)v1; o[2] = (bf16_t)v2; o[3] = (bf16_t)v3;
-        *reinterpret_cast<bf16x4 *>(p.out + tok * p.ld_out + f) = o;
+      }
+      lds_barrier();
+      constexpr int CPR = BN / 8;   // 16-byte chunks per tile row
+#pragma unroll 8
+      for (int idx = tid; idx < BM * CPR; idx += 256) {
+        const int rl = idx / CPR, c = idx - rl * CPR;
+        const int64_t tok = my_row0 + rl;
+        const int f = my_col0 + c * 8;
+        if (tok < p.N && f < p.n)
+          *reinterpret_cast<uint4 *>(p.out + tok * p.ld_out + f) =
+              *reinterpret_cast<const uint4 *>(smem + rl * C::PITCH_BF16 + c * 16);
+      }
+    } else {
+      // gated residual: the raw accumulators are staged in two halves of BM/2 rows (an fp32
+      // tile does not fit LDS in one piece); bias, gate and the update of x happen on the way
+      // out, on whole-row pieces
+      constexpr int HB = TM / 2;        // token tiles per wave per half
+      constexpr int HROWS = BM / 2;     // rows per half: wave-row wm owns HB*32 of them
+      constexpr int CPR = BN / 4;       // float4 chunks per tile row
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+#pragma unroll
+        for (int bb = 0; bb < HB; ++bb) {
+          const int b = half * HB + bb;
+          const int rl = wm * (HB * 32) + bb * 32 + l32;             // row inside the half
+#pragma unroll
+          for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const int fl = wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;
+              *reinterpret_cast<float4 *>(smem + rl * C::PITCH_F32 + fl * 4) =
+                  make_float4(acc[a][b][4 * g + 0], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]);
+            }
+        }
+        lds_barrier();
+#pragma unroll 6
+        for (int idx = tid; idx < HROWS * CPR; idx += 256) {
+          const int rl = idx / CPR, c = idx - rl * CPR;
+          const int wrow = rl / (HB * 32), within = rl - wrow * (HB * 32);
+          const int64_t tok = my_row0 + wrow * (BM / 2) + half * (HB * 32) + within;
+          const int f = my_col0 + c * 4;
+          if (tok < p.N && f < p.n) {
+            float4 *rp = reinterpret_cast<float4 *>(p.resid + tok * (int64_t)p.n + f);
+            float4 r = *rp;
+            float4 v = *reinterpret_cast<const float4 *>(smem + rl * C::PITCH_F32 + c * 16);
+            if (p.gate_tab) {
+              float4 gt = *reinterpret_cast<const float4 *>(p.gate_tab + f);
+              if (p.gate_c6) {
+                const float4 gc =
+                    *reinterpret_cast<const float4 *>(p.gate_c6 + (tok / p.tokens_per_sample) * p.gate_c6_stride + f);
+                gt.x += gc.x; gt.y += gc.y; gt.z += gc.z; gt.w += gc.w;
+              }
+              v.x *= gt.x; v.y *= gt.y; v.z *= gt.z; v.w *= gt.w;
+            }
+            r.x += v.x; r.y += v.y; r.z += v.z; r.w += v.w;
+            *rp = r;
+            if (p.out) {
+              bf16x4 o;
+              o[0] = (bf16_t)r.x; o[1] = (bf16_t)r.y; o[2] = (bf16_t)r.z; o[3] = (bf16_t)r.w;
+              *reinterpret_cast<bf16x4 *>(p.out + tok * p.ld_out + f) = o;
+            }
+          }
+        }
+        lds_barrier();   // the staging area is rewritten by the next half / the next tile's prologue
       }
     }
+    if (!more) break;
+    if constexpr (EPI != 2) lds_barrier();   // staged rows are read by other waves until here
+    tile = next_tile;
   }
+#undef GEMM_SET_TILE
+#undef GEMM_BIAS_LOAD
+#undef GEMM_G_LOAD
+#undef GEMM_G_LOAD_FULL
+#undef GEMM_S_STORE
+#undef GEMM_READ_FRAGS
+#undef GEMM_MFMAS
+}
+
+int num_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cus = prop.multiProcessorCount;
+    if (cus <= 0) cus = 256;
+  }
+  return cus;
 }
 
 template <int BM, int BN, int EPI>
 int launch_one(const GemmParams &p0, hipStream_t s) {
+  using C = GemmCfg<BM, BN>;
   GemmParams p = p0;
   const int64_t tiles_m = (p.N + BM - 1) / BM;
   p.tiles_n = (p.n + BN - 1) / BN;
-  p.total_tiles = tiles_m * p.tiles_n;
-  constexpr int smem = 2 * (BM + BN) * ROW_BYTES;
+  const int64_t total = tiles_m * p.tiles_n;
+  if (total > (int64_t)1 << 30) {
+    ddit::set_error("linear: %lld output tiles: too many", (long long)total);
+    return -2;
+  }
+  p.total_tiles = (int)total;
+  // one workgroup per CU (the LDS stages leave room for one); a multiple of 8 so that every
+  // round gives each XCD a contiguous run of tiles
+  int grid = num_cus() & ~7;
+  if (grid < 8) grid = 8;
+  if (total <= grid) grid = (int)((total + 7) & ~(int64_t)7);
+  p.rounds = (int)((total + grid - 1) / grid);
   static bool attr_set = false;  // benign race: the attribute is idempotent
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<BM, BN, EPI>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
     if (e != hipSuccess) return ddit::hip_fail(e, "gemm hipFuncSetAttribute");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_gemm_bf16<BM, BN, EPI>), dim3((unsigned)p.total_tiles), dim3(256), smem, s, p);
+  hipLaunchKernelGGL((k_gemm_bf16<BM, BN, EPI>), dim3((unsigned)grid), dim3(256), C::SMEM, s, p);
   return ddit::hip_fail(hipGetLastError(), "gemm launch");
 }
 
@@ -235,6 +469,14 @@ namespace ddit {
 
 int launch_gemm(int epilogue, const GemmArgs &a, hipStream_t s) {
   if (a.N == 0 || a.n == 0) return 0;
+  if ((int64_t)a.n * a.k >= (int64_t)1 << 31) {
+    set_error("linear: n*k = %lld exceeds the 32-bit weight index range", (long long)a.n * a.k);
+    return -2;
+  }
+  if (a.N * a.ld_u >= (int64_t)1 << 31) {
+    set_error("linear: N*ld_u = %lld exceeds the 31-bit activation index range", (long long)(a.N * a.ld_u));
+    return -2;
+  }
   GemmParams p;
   p.u = reinterpret_cast<const bf16_t *>(a.u); p.ld_u = a.ld_u;
   p.W = reinterpret_cast<const bf16_t *>(a.W);
@@ -244,7 +486,7 @@ int launch_gemm(int epilogue, const GemmArgs &a, hipStream_t s) {
   p.resid = a.resid;
   p.gate_tab = a.gate_tab; p.gate_c6 = a.gate_c6; p.gate_c6_stride = a.gate_c6_stride;
   p.tokens_per_sample = a.tokens_per_sample > 0 ? a.tokens_per_sample : 1;
-  p.tiles_n = 0; p.total_tiles = 0;
+  p.tiles_n = 0; p.total_tiles = 0; p.rounds = 0;
   switch (epilogue) {
     case 0: return launch_epi<0>(p, s);
     case 1: return launch_epi<1>(p, s);
