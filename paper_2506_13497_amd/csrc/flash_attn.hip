@@ -21,19 +21,24 @@
 // operand of O^T = V^T P^T, provided V^T's key axis is enumerated in the same order:
 // V is transposed on its way into LDS (two keys packed per 32-bit write) with the keys
 // of each group of 16 stored in the order the accumulator registers enumerate them.
-// The head dim 72 is padded to 80 for Q K^T (zeros in LDS, never in HBM) and to 96 rows
-// for V^T; one of the spare V^T rows is set to 1 so that the same MFMAs that form O also
-// accumulate the softmax denominator (of the bf16-rounded probabilities actually used).
+// The head dim 72 is padded to 80 for Q K^T (zeros in registers, never in memory) and to
+// 96 rows for V^T; one of the spare V^T rows is set to 1 so that the same MFMAs that form
+// O also accumulate the softmax denominator (of the bf16-rounded probabilities used).
 //
-// LDS rows are padded by 16 bytes (K: 176 B, V^T: 144 B) so that a 16-byte read of 8
-// consecutive rows covers all 32 banks once.  Two stages; the next tile's global loads
-// are in flight during the current tile's MFMAs; one barrier per tile.
+// Data movement.  K tiles go global -> LDS directly (16 bytes per lane, no registers),
+// packed at a 144-byte row pitch for dh 72 (16-byte reads of 8 consecutive rows then
+// cover all 32 banks once) or at 128 bytes with an XOR chunk swizzle for dh 64.  V goes
+// through registers for the transposition.  Two stages; the next tile's loads are in
+// flight during the current tile's MFMAs; one barrier per tile.
 #include "ddit_common.hpp"
 
 namespace {
 
 constexpr int QT = 128;   // queries per workgroup
 constexpr int KT = 64;    // keys per LDS tile
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+typedef __attribute__((address_space(1))) const void *gbl_ptr_t;
 
 struct FlashParams {
   const bf16_t *q, *k, *v;
@@ -53,22 +58,27 @@ struct FlashParams {
 template <int DH>
 struct Cfg {
   static constexpr int KS = (DH + 15) / 16;        // k-steps of Q K^T
-  static constexpr int DCH = DH / 8;               // 16-byte chunks per row in HBM
-  static constexpr int KROW = KS * 32 + 16;        // K row stride in LDS (bytes)
+  static constexpr int DCH = DH / 8;               // 16-byte chunks per K/V row
+  static constexpr int KROW = DCH * 16;            // K row pitch in LDS: packed
+  static constexpr bool SWZ = (KROW % 128) == 0;   // packed pitch would alias banks: swizzle chunks
   static constexpr bool ONES = (DH % 32) != 0;     // a spare V^T row exists for the row sum
   static constexpr int DT = (DH + 31) / 32;        // 32-row tiles of V^T
-  static constexpr int VROW = KT * 2 + 16;         // V^T row stride (bytes)
+  static constexpr int VROW = KT * 2 + 16;         // V^T row pitch (bytes)
   static constexpr int K_BYTES = KT * KROW;
   static constexpr int V_BYTES = DT * 32 * VROW;
   static constexpr int STAGE = K_BYTES + V_BYTES;
+  static constexpr int K_INSTR = K_BYTES / 1024;   // wave-wide 16-byte direct loads per K tile
+  static_assert(K_BYTES % 1024 == 0, "K tile must be a whole number of wave loads");
 };
 
 // position of key offset o (0..15) inside its group of 16 in the V^T rows:
 // o = 8 g + 4 h + e  ->  8 h + 4 g + e   (h: lane half, g: accumulator group parity)
 __device__ __forceinline__ int key_pos16(int o) { return ((o & 4) << 1) | ((o & 8) >> 1) | (o & 3); }
 
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <int DH>
-__global__ __launch_bounds__(256) void k_flash_attn(FlashParams p) {
+__global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
   using C = Cfg<DH>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -79,8 +89,11 @@ __global__ __launch_bounds__(256) void k_flash_attn(FlashParams p) {
   const int64_t q_tok0 = p.q_outer * g_out + p.q_inner * g_in;
   const int64_t kv_tok0 = p.kv_outer * g_out + p.kv_inner * g_in;
   const int q0 = blockIdx.x * QT + wave * 32;
+  const bf16_t *kbase = p.k + kv_tok0 * p.ld_kv + h * DH;
+  const bf16_t *vbase = p.v + kv_tok0 * p.ld_kv + h * DH;
+  const int64_t kv_row = p.kv_tok_step * p.ld_kv;   // elements between consecutive keys
 
-  // ---- Q fragment: lane holds query l32, d = 16 ks + 8 lh .. +7
+  // ---- Q fragment: lane holds query l32, d = 16 ks + 8 lh .. +7 (zeros past DH)
   bf16x8 qf[C::KS];
   {
     int qi = q0 + l32;
@@ -89,22 +102,15 @@ __global__ __launch_bounds__(256) void k_flash_attn(FlashParams p) {
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
       const int d0 = 16 * ks + 8 * lh;
-      if (d0 < DH) {
-        qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + d0);
-      } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) qf[ks][e] = (bf16_t)0.f;
-      }
+      for (int e = 0; e < 8; ++e) qf[ks][e] = (bf16_t)0.f;
+      if (d0 < DH) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + d0);
     }
   }
 
-  // ---- zero the padding of both stages once (K chunk DH/8.., V^T rows DH..), set the ones row
-  for (int i = tid; i < 2 * KT; i += 256) {
-    unsigned char *kr = smem + (i / KT) * C::STAGE + (i % KT) * C::KROW;
-    for (int c = C::DCH; c < C::KS * 2; ++c) *reinterpret_cast<uint4 *>(kr + c * 16) = make_uint4(0, 0, 0, 0);
-  }
+  // ---- V^T padding rows (DH .. 32 DT - 1) of both stages: zero, except the row of ones
   if constexpr (C::DT * 32 > DH) {
-    constexpr int PER_STAGE = (C::DT * 32 - DH) * (KT / 2);   // 32-bit words of V^T padding
+    constexpr int PER_STAGE = (C::DT * 32 - DH) * (KT / 2);   // 32-bit words
     for (int i = tid; i < 2 * PER_STAGE; i += 256) {
       const int st = i / PER_STAGE, rem = i % PER_STAGE;
       const int row = DH + rem / (KT / 2), w = rem % (KT / 2);
@@ -113,66 +119,68 @@ __global__ __launch_bounds__(256) void k_flash_attn(FlashParams p) {
     }
   }
 
-  // ---- global -> register staging of one K/V tile
-  constexpr int K_TASKS = KT * C::DCH;            // 16-byte chunks of K
-  constexpr int V_TASKS = (KT / 2) * C::DCH;      // key pairs x chunks
-  constexpr int K_PER = (K_TASKS + 255) / 256;
-  constexpr int V_PER = (V_TASKS + 255) / 256;
-  uint4 k_reg[K_PER], v_reg[V_PER][2];
+  // ---- K tile, global -> LDS: wave-wide load j fills LDS bytes [1024 j, 1024 j + 1024) of the tile;
+  // this lane's piece is LDS chunk m = 64 j + lane = (key m / DCH, chunk slot m % DCH)
+  constexpr int KJ = (C::K_INSTR + 3) / 4;   // loads per wave (the last one only on some waves)
+  int k_key[KJ], k_col[KJ];
+#pragma unroll
+  for (int i = 0; i < KJ; ++i) {
+    const int m = 64 * (wave + 4 * i) + lane;
+    const int key = m / C::DCH, slot = m - key * C::DCH;
+    k_key[i] = key;
+    k_col[i] = (C::SWZ ? (slot ^ (key & 7)) : slot) * 8;
+  }
+  // ---- V tile through registers: task A (every lane): key pair kp = l32, chunk 2 wave + lh;
+  // task B (dh 72 only: the 9th chunk): lanes 0..31 of wave (tile & 3)
+  constexpr bool VB = (C::DCH % 8) != 0;
+  const int v_pos = ((2 * l32) & ~15) | key_pos16((2 * l32) & 15);   // even: the pair stays adjacent
+  uint4 va0, va1, vb0, vb1;
+  va0 = va1 = vb0 = vb1 = make_uint4(0u, 0u, 0u, 0u);
 
-  auto g_load = [&](int key0) {
-#pragma unroll
-    for (int i = 0; i < K_PER; ++i) {
-      const int t = tid + 256 * i;
-      if (t < K_TASKS) {
-        int key = key0 + t / C::DCH;
-        if (key > Lk - 1) key = Lk - 1;   // tail keys re-read the last valid key; masked below
-        k_reg[i] = *reinterpret_cast<const uint4 *>(p.k + (kv_tok0 + (int64_t)key * p.kv_tok_step) * p.ld_kv +
-                                                    h * DH + (t % C::DCH) * 8);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < V_PER; ++i) {
-      const int t = tid + 256 * i;
-      if (t < V_TASKS) {
-        const int kp = t % (KT / 2), dc = t / (KT / 2);
-        int key_a = key0 + 2 * kp, key_b = key_a + 1;
-        if (key_a > Lk - 1) key_a = Lk - 1;
-        if (key_b > Lk - 1) key_b = Lk - 1;
-        v_reg[i][0] = *reinterpret_cast<const uint4 *>(p.v + (kv_tok0 + (int64_t)key_a * p.kv_tok_step) * p.ld_kv +
-                                                       h * DH + dc * 8);
-        v_reg[i][1] = *reinterpret_cast<const uint4 *>(p.v + (kv_tok0 + (int64_t)key_b * p.kv_tok_step) * p.ld_kv +
-                                                       h * DH + dc * 8);
-      }
-    }
-  };
-  auto s_store = [&](int stage) {
-    unsigned char *sk = smem + stage * C::STAGE;
-    unsigned char *sv = sk + C::K_BYTES;
-#pragma unroll
-    for (int i = 0; i < K_PER; ++i) {
-      const int t = tid + 256 * i;
-      if (t < K_TASKS) *reinterpret_cast<uint4 *>(sk + (t / C::DCH) * C::KROW + (t % C::DCH) * 16) = k_reg[i];
-    }
-#pragma unroll
-    for (int i = 0; i < V_PER; ++i) {
-      const int t = tid + 256 * i;
-      if (t < V_TASKS) {
-        const int kp = t % (KT / 2), dc = t / (KT / 2);
-        const int ko = 2 * kp;                                   // even key offset in the tile
-        const int pos = (ko & ~15) | key_pos16(ko & 15);         // even: the pair stays adjacent
-        const uint32_t a[4] = {v_reg[i][0].x, v_reg[i][0].y, v_reg[i][0].z, v_reg[i][0].w};
-        const uint32_t b[4] = {v_reg[i][1].x, v_reg[i][1].y, v_reg[i][1].z, v_reg[i][1].w};
-        unsigned char *dst = sv + (dc * 8) * C::VROW + pos * 2;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          // d = 8 dc + 2j: low halves; d = 8 dc + 2j + 1: high halves
-          *reinterpret_cast<uint32_t *>(dst + (2 * j) * C::VROW) = (a[j] & 0xFFFFu) | (b[j] << 16);
-          *reinterpret_cast<uint32_t *>(dst + (2 * j + 1) * C::VROW) = (a[j] >> 16) | (b[j] & 0xFFFF0000u);
-        }
-      }
-    }
-  };
+#define FA_LOAD_TILE(KEY0, STAGE_IDX, TILE_IDX)                                                         \
+  do {                                                                                                  \
+    _Pragma("unroll") for (int i = 0; i < KJ; ++i) {                                                    \
+      if (wave + 4 * i < C::K_INSTR) {                                                                  \
+        int key_ = (KEY0) + k_key[i];                                                                   \
+        if (key_ > Lk - 1) key_ = Lk - 1; /* tail keys re-read the last valid key; masked below */      \
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kbase + key_ * kv_row + k_col[i]),                 \
+                                         (lds_ptr_t)(smem + (STAGE_IDX) * C::STAGE + (wave + 4 * i) * 1024), \
+                                         16, 0, 0);                                                     \
+      }                                                                                                 \
+    }                                                                                                   \
+    {                                                                                                   \
+      int ka_ = (KEY0) + 2 * l32, kb_ = ka_ + 1;                                                        \
+      if (ka_ > Lk - 1) ka_ = Lk - 1;                                                                   \
+      if (kb_ > Lk - 1) kb_ = Lk - 1;                                                                   \
+      const int dc_ = 2 * wave + lh;                                                                    \
+      va0 = *reinterpret_cast<const uint4 *>(vbase + ka_ * kv_row + dc_ * 8);                           \
+      va1 = *reinterpret_cast<const uint4 *>(vbase + kb_ * kv_row + dc_ * 8);                           \
+      if (VB && wave == ((TILE_IDX) & 3) && lh == 0) {                                                  \
+        vb0 = *reinterpret_cast<const uint4 *>(vbase + ka_ * kv_row + 64);                              \
+        vb1 = *reinterpret_cast<const uint4 *>(vbase + kb_ * kv_row + 64);                              \
+      }                                                                                                 \
+    }                                                                                                   \
+  } while (0)
+
+#define FA_VT_WRITE(DST, A, B)                                                                          \
+  do {                                                                                                  \
+    unsigned char *d_ = (DST);                                                                          \
+    *reinterpret_cast<uint32_t *>(d_ + 0 * C::VROW) = ((A).x & 0xFFFFu) | ((B).x << 16);               \
+    *reinterpret_cast<uint32_t *>(d_ + 1 * C::VROW) = ((A).x >> 16) | ((B).x & 0xFFFF0000u);           \
+    *reinterpret_cast<uint32_t *>(d_ + 2 * C::VROW) = ((A).y & 0xFFFFu) | ((B).y << 16);               \
+    *reinterpret_cast<uint32_t *>(d_ + 3 * C::VROW) = ((A).y >> 16) | ((B).y & 0xFFFF0000u);           \
+    *reinterpret_cast<uint32_t *>(d_ + 4 * C::VROW) = ((A).z & 0xFFFFu) | ((B).z << 16);               \
+    *reinterpret_cast<uint32_t *>(d_ + 5 * C::VROW) = ((A).z >> 16) | ((B).z & 0xFFFF0000u);           \
+    *reinterpret_cast<uint32_t *>(d_ + 6 * C::VROW) = ((A).w & 0xFFFFu) | ((B).w << 16);               \
+    *reinterpret_cast<uint32_t *>(d_ + 7 * C::VROW) = ((A).w >> 16) | ((B).w & 0xFFFF0000u);           \
+  } while (0)
+
+#define FA_STORE_V(STAGE_IDX, TILE_IDX)                                                                 \
+  do {                                                                                                  \
+    unsigned char *sv_ = smem + (STAGE_IDX) * C::STAGE + C::K_BYTES + v_pos * 2;                        \
+    FA_VT_WRITE(sv_ + (2 * wave + lh) * 8 * C::VROW, va0, va1);                                         \
+    if (VB && wave == ((TILE_IDX) & 3) && lh == 0) FA_VT_WRITE(sv_ + 64 * C::VROW, vb0, vb1);           \
+  } while (0)
 
   floatx16 oacc[C::DT];
 #pragma unroll
@@ -183,11 +191,11 @@ __global__ __launch_bounds__(256) void k_flash_attn(FlashParams p) {
   float l_run = 0.f;         // running sum (only used when there is no ones row)
 
   const int n_tiles = (Lk + KT - 1) / KT;
-  g_load(0);
-  __syncthreads();           // padding writes done before tile data lands next to them
-  s_store(0);
-  if (n_tiles > 1) g_load(KT);
-  __syncthreads();
+  FA_LOAD_TILE(0, 0, 0);
+  FA_STORE_V(0, 0);
+  if (n_tiles > 1) FA_LOAD_TILE(KT, 1, 1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // K of tile 0 has landed (once per kernel: also waits tile 1)
+  lds_barrier();
 
   for (int it = 0; it < n_tiles; ++it) {
     const int cur = it & 1;
@@ -200,9 +208,15 @@ __global__ __launch_bounds__(256) void k_flash_attn(FlashParams p) {
     for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[kt][e] = 0.f;
+      const int row = kt * 32 + l32;
 #pragma unroll
       for (int ks = 0; ks < C::KS; ++ks) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(sk + (kt * 32 + l32) * C::KROW + (2 * ks + lh) * 16);
+        const int c = 2 * ks + lh;
+        bf16x8 kf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) kf[e] = (bf16_t)0.f;
+        if (c < C::DCH)
+          kf = *reinterpret_cast<const bf16x8 *>(sk + row * C::KROW + (C::SWZ ? (c ^ (row & 7)) : c) * 16);
         s[kt] = mfma32(kf, qf[ks], s[kt]);
       }
     }
@@ -225,9 +239,7 @@ __global__ __launch_bounds__(256) void k_flash_attn(FlashParams p) {
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2);
     const float mb = m_new * p.scale_log2;
-    m_run = m_new;
     bf16x8 pf[4];
     float psum = 0.f;
 #pragma unroll
@@ -239,11 +251,16 @@ __global__ __launch_bounds__(256) void k_flash_attn(FlashParams p) {
         pf[kt * 2 + (r >> 3)][r & 7] = pb;
         if (!C::ONES) psum += (float)pb;
       }
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // some query of the wave has a new maximum
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2);
 #pragma unroll
-    for (int d = 0; d < C::DT; ++d)
+      for (int d = 0; d < C::DT; ++d)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[d][e] *= alpha;
-    if (!C::ONES) l_run = l_run * alpha + psum;
+        for (int e = 0; e < 16; ++e) oacc[d][e] *= alpha;
+      if (!C::ONES) l_run *= alpha;
+      m_run = m_new;
+    }
+    if (!C::ONES) l_run += psum;
 
     // ---- O^T += V^T P^T
 #pragma unroll
@@ -255,10 +272,14 @@ __global__ __launch_bounds__(256) void k_flash_attn(FlashParams p) {
       }
     }
 
-    if (it + 1 < n_tiles) s_store(cur ^ 1);
-    if (it + 2 < n_tiles) g_load((it + 2) * KT);
-    __syncthreads();
+    if (it + 1 < n_tiles) FA_STORE_V(cur ^ 1, it + 1);           // registers hold V of tile it+1
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // K of tile it+1 has landed
+    lds_barrier();                                               // stage cur is free, stage cur^1 complete
+    if (it + 2 < n_tiles) FA_LOAD_TILE((it + 2) * KT, cur, it + 2);
   }
+#undef FA_LOAD_TILE
+#undef FA_VT_WRITE
+#undef FA_STORE_V
 
   // ---- row sum
   float l_tot;
