@@ -1,0 +1,163 @@
+"""Host-side tests of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments with the documented status codes before anything is
+enqueued (so no HIP call happens on these paths)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2506_13497_amd", "libddit_hot.so")
+HEADER = os.path.join(ROOT, "include", "ddit_hot.h")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libddit_hot.so not built (run __graft_entry__.build())")
+
+
+@pytest.fixture(scope="module")
+def m():
+    import paper_2506_13497_amd as mod
+    return mod
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(ddit_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol(m):
+    lib = C.CDLL(LIB)
+    names = _declared_functions()
+    assert {"ddit_attn_fwd", "ddit_stdit_block_fwd", "ddit_denoise_step"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), "missing export " + n
+    assert sorted(m.binding.EXPORTS) == names
+    assert m.ddit_abi_version() == 1
+
+
+def test_status_strings(m):
+    assert m.ddit_status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert m.ddit_status_string(code) not in ("ok", "unknown status")
+    assert m.ddit_status_string(-99) == "unknown status"
+
+
+def _shape(m, **kw):
+    d = dict(B=1, T=4, Hp=8, Wp=8, D=256, H=4, dh=64, M=1024, Ly=16, n_blocks=1)
+    d.update(kw)
+    return m.make_shape(**d)
+
+
+def test_workspace_bytes_and_layout_monotone(m):
+    small = m.ddit_workspace_bytes(_shape(m))
+    big = m.ddit_workspace_bytes(_shape(m, T=8))
+    taps = m.ddit_workspace_bytes(_shape(m, flags=m.DDIT_FLAG_TAPS))
+    assert 0 < small < big and taps > small
+    # the fixed part: x fp32 + xh + qkv + o + kvc + h (+ conditioning), each 256-byte aligned
+    N, D, A, M_, Ly = 256, 256, 256, 1024, 16
+    lower = N * D * 4 + N * D * 2 + N * 3 * A * 2 + N * A * 2 + Ly * 2 * A * 2 + N * M_ * 2
+    assert lower <= small <= lower + 64 * 1024
+    off, nb = m.ddit_tap_region(_shape(m, flags=m.DDIT_FLAG_TAPS), 1, m.TAP_NAMES.index("h"))
+    assert nb == N * M_ * 2 and off % 256 == 0 and off + nb <= taps
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(dh=80), -2), (dict(H=8, dh=64), -2), (dict(D=250), -2), (dict(B=0), -1), (dict(Ly=0), -1),
+    (dict(B=65), -2), (dict(D=8192, H=4), -2),
+])
+def test_bad_shapes_are_rejected(m, kw, code):
+    with pytest.raises(m.binding.DditError) as e:
+        m.ddit_workspace_bytes(_shape(m, **kw))
+    assert e.value.status == code and len(str(e.value)) > 20
+
+
+def test_struct_size_versions_the_shape(m):
+    sh = _shape(m)
+    sh.struct_size = 12
+    with pytest.raises(m.binding.DditError) as e:
+        m.ddit_workspace_bytes(sh)
+    assert e.value.status == -1 and "struct_size" in str(e.value)
+
+
+def test_tap_region_needs_flag(m):
+    with pytest.raises(m.binding.DditError) as e:
+        m.ddit_tap_region(_shape(m), 0, 0)
+    assert e.value.status == -1
+
+
+class _FakeTensor:
+    """Stands in for a device tensor on the validation-only paths: just an address and a size."""
+    def __init__(self, addr, nbytes=1 << 20):
+        self._a, self._n = addr, nbytes
+
+    def data_ptr(self):
+        return self._a
+
+    def numel(self):
+        return self._n
+
+    def element_size(self):
+        return 1
+
+
+def _call_attn(m, q=0x10000, k=0x20000, v=0x30000, o=0x40000, ld=256, valid=None, kind=0, shape=None):
+    lib = m.binding._lib
+    sh = shape or _shape(m)
+    vl = None if valid is None else (C.c_int32 * len(valid))(*valid)
+    return lib.ddit_attn_fwd(kind, C.byref(sh), C.c_void_p(q), C.c_void_p(k), C.c_void_p(v), ld, ld, vl,
+                             C.c_void_p(o), ld, None, None, 0, None)
+
+
+def test_attn_argument_validation_happens_before_any_launch(m):
+    assert _call_attn(m, q=0) == -1                       # NULL pointer
+    assert _call_attn(m, q=0x10008) == -4                 # misaligned
+    assert _call_attn(m, ld=128) == -1                    # leading dimension below H*dh
+    assert _call_attn(m, ld=260) == -4                    # not a multiple of 8
+    assert _call_attn(m, kind=7) == -1
+    assert _call_attn(m, kind=2, valid=[0]) == -1         # valid_len below 1
+    assert _call_attn(m, kind=2, valid=[17]) == -1        # above Ly
+    assert "valid_len" in m.ddit_last_error()
+
+
+def test_block_and_step_validation(m):
+    lib = m.binding._lib
+    sh = _shape(m)
+    need = m.ddit_workspace_bytes(sh)
+    wb = m.binding.ddit_block_weights()
+    P = C.c_void_p
+    # NULL weights / c6
+    assert lib.ddit_stdit_block_fwd(C.byref(sh), None, P(0x1000), P(0x2000), None, P(0x3000), P(0x4000), P(0x100000), need, None) == -1
+    # workspace too small: message carries the required size
+    assert lib.ddit_stdit_block_fwd(C.byref(sh), C.byref(wb), P(0x1000), P(0x2000), None, P(0x3000), P(0x4000), P(0x100000), need - 1, None) == -3
+    assert str(need) in m.ddit_last_error()
+    # NULL workspace
+    assert lib.ddit_stdit_block_fwd(C.byref(sh), C.byref(wb), P(0x1000), P(0x2000), None, P(0x3000), P(0x4000), None, 0, None) == -3
+    # workspace fine, but the (all-NULL) layer weights are rejected by name
+    assert lib.ddit_stdit_block_fwd(C.byref(sh), C.byref(wb), P(0x1000), P(0x2000), None, P(0x3000), P(0x4000), P(0x100000), need, None) == -1
+    assert "w_qkv" in m.ddit_last_error()
+    # misaligned x_in
+    assert lib.ddit_stdit_block_fwd(C.byref(sh), C.byref(wb), P(0x1004), P(0x2000), None, P(0x3000), P(0x4000), P(0x100000), need, None) == -4
+    # step: NULL weights struct
+    assert lib.ddit_denoise_step(C.byref(sh), None, P(0x1000), P(0x2000), None, None, None, P(0x4000), P(0x100000), need, None) == -1
+
+
+def test_linear_and_layernorm_validation(m):
+    lib = m.binding._lib
+    P = C.c_void_p
+    assert lib.ddit_linear_fwd(0, P(0x1000), 64, P(0x2000), None, 16, 64, 64, None, 64, None, None, None, -1, 1, None) == -1   # no out
+    assert lib.ddit_linear_fwd(0, P(0x1000), 60, P(0x2000), None, 16, 64, 64, P(0x3000), 64, None, None, None, -1, 1, None) == -1  # ld_u < k
+    assert lib.ddit_linear_fwd(0, P(0x1000), 64, P(0x2000), None, 16, 60, 64, P(0x3000), 64, None, None, None, -1, 1, None) == -2  # n % 8
+    assert lib.ddit_linear_fwd(2, P(0x1000), 64, P(0x2000), None, 16, 64, 64, None, 0, None, None, None, -1, 1, None) == -1      # no resid
+    assert lib.ddit_linear_fwd(2, P(0x1000), 64, P(0x2000), None, 16, 64, 64, None, 0, P(0x5000), None, None, 2, 1, None) == -1  # gate w/o table
+    assert lib.ddit_linear_fwd(9, P(0x1000), 64, P(0x2000), None, 16, 64, 64, P(0x3000), 64, None, None, None, -1, 1, None) == -1
+    assert lib.ddit_modulated_layernorm_fwd(P(0x1000), P(0x2000), P(0x3000), 2, 4, 4, 64, 1e-6, P(0x4000), None) == -1  # which
+    assert lib.ddit_modulated_layernorm_fwd(P(0x1000), P(0x2000), P(0x3000), 0, 4, 4, 60, 1e-6, P(0x4000), None) == -2  # D % 8
+    assert lib.ddit_modulated_layernorm_fwd(None, P(0x2000), P(0x3000), 0, 4, 4, 64, 1e-6, P(0x4000), None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
