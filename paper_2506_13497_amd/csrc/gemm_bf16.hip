@@ -166,6 +166,31 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
     }                                                                                              \
   } while (0)
 
+  // Gate vectors of the tile's out-features for the (at most two) samples its rows belong to, kept
+  // in LDS past the stages: slot 0 = sample of the tile's first row, slot 1 = the next sample.
+  float4 gate_reg = make_float4(1.f, 1.f, 1.f, 1.f);
+  float *smem_gate = reinterpret_cast<float *>(smem + C::SMEM);
+  int64_t tile_sample0 = 0;      // sample of the first row of the tile whose gate is in gate_reg
+#define GEMM_GATE_LOAD()                                                                           \
+  do {                                                                                             \
+    if (EPI == 2 && p.gate_tab) {                                                                  \
+      tile_sample0 = row0 / p.tokens_per_sample;                                                   \
+      if (tid < 2 * (BN / 4)) {                                                                    \
+        const int which_ = tid / (BN / 4), c_ = tid - which_ * (BN / 4);                           \
+        int f_ = col0 + 4 * c_;                                                                    \
+        if (f_ > p.n - 4) f_ = p.n - 4;                                                            \
+        gate_reg = *reinterpret_cast<const float4 *>(p.gate_tab + f_);                             \
+        if (p.gate_c6) {                                                                           \
+          int64_t smp_ = tile_sample0 + which_;                                                    \
+          const int64_t last_ = (p.N - 1) / p.tokens_per_sample;                                   \
+          if (smp_ > last_) smp_ = last_;                                                          \
+          const float4 gc_ = *reinterpret_cast<const float4 *>(p.gate_c6 + smp_ * p.gate_c6_stride + f_); \
+          gate_reg.x += gc_.x; gate_reg.y += gc_.y; gate_reg.z += gc_.z; gate_reg.w += gc_.w;      \
+        }                                                                                          \
+      }                                                                                            \
+    }                                                                                              \
+  } while (0)
+
 #define GEMM_BIAS_LOAD()                                                                           \
   do {                                                                                             \
     if (p.bias) {                                                                                  \
@@ -233,13 +258,16 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
   if (tile >= p.total_tiles) return;
   GEMM_SET_TILE(tile);
   GEMM_BIAS_LOAD();
+  GEMM_GATE_LOAD();
   GEMM_G_LOAD(0);
 
   for (int round = 0;; ++round) {
     // ---- prologue: the registers hold k-step 0 of this tile
     const int64_t my_row0 = row0;
     const int my_col0 = col0;
+    const int64_t my_sample0 = tile_sample0;
     GEMM_S_STORE(0);
+    if (EPI == 2 && tid < 2 * (BN / 4)) *reinterpret_cast<float4 *>(smem_gate + tid * 4) = gate_reg;
     if (nk > 1) GEMM_G_LOAD(BK);
     floatx16 acc[TN][TM];
 #pragma unroll
@@ -311,6 +339,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
     if (more) {
       GEMM_SET_TILE(next_tile);
       GEMM_BIAS_LOAD();
+      GEMM_GATE_LOAD();
       GEMM_G_LOAD(0);
     }
 
@@ -353,6 +382,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
       constexpr int HB = TM / 2;        // token tiles per wave per half
       constexpr int HROWS = BM / 2;     // rows per half: wave-row wm owns HB*32 of them
       constexpr int CPR = BN / 4;       // float4 chunks per tile row
+      const int64_t sample1_tok = (my_sample0 + 1) * p.tokens_per_sample;   // first token of the tile's second sample
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
 #pragma unroll
@@ -369,31 +399,58 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
             }
         }
         lds_barrier();
-#pragma unroll 6
-        for (int idx = tid; idx < HROWS * CPR; idx += 256) {
-          const int rl = idx / CPR, c = idx - rl * CPR;
-          const int wrow = rl / (HB * 32), within = rl - wrow * (HB * 32);
-          const int64_t tok = my_row0 + wrow * (BM / 2) + half * (HB * 32) + within;
-          const int f = my_col0 + c * 4;
-          if (tok < p.N && f < p.n) {
-            float4 *rp = reinterpret_cast<float4 *>(p.resid + tok * (int64_t)p.n + f);
-            float4 r = *rp;
-            float4 v = *reinterpret_cast<const float4 *>(smem + rl * C::PITCH_F32 + c * 16);
-            if (p.gate_tab) {
-              float4 gt = *reinterpret_cast<const float4 *>(p.gate_tab + f);
-              if (p.gate_c6) {
-                const float4 gc =
-                    *reinterpret_cast<const float4 *>(p.gate_c6 + (tok / p.tokens_per_sample) * p.gate_c6_stride + f);
-                gt.x += gc.x; gt.y += gc.y; gt.z += gc.z; gt.w += gc.w;
+        // Loads of x are batched ahead of the stores (the compiler must assume that a store to
+        // the stream may alias a later load from it, so it would serialise them one by one).
+        constexpr int ITERS = HROWS * CPR / 256;
+        constexpr int UB = ITERS % 8 == 0 ? 8 : (ITERS % 6 == 0 ? 6 : (ITERS % 4 == 0 ? 4 : 1));
+        static_assert(HROWS * CPR % 256 == 0, "row pieces must divide evenly over the threads");
+#pragma unroll 1
+        for (int it0 = 0; it0 < ITERS; it0 += UB) {
+          float4 xr[UB];
+          int64_t off[UB];
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            const int idx = tid + 256 * (it0 + u);
+            const int rl = idx / CPR, c = idx - rl * CPR;
+            const int wrow = rl / (HB * 32), within = rl - wrow * (HB * 32);
+            const int64_t tok = my_row0 + wrow * (BM / 2) + half * (HB * 32) + within;
+            const int f = my_col0 + c * 4;
+            const bool ok = tok < p.N && f < p.n;
+            off[u] = ok ? tok * (int64_t)p.n + f : -1;
+            xr[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ok) xr[u] = *reinterpret_cast<const float4 *>(p.resid + off[u]);
+          }
+#pragma unroll
+          for (int u = 0; u < UB; ++u) {
+            if (off[u] >= 0) {
+              const int idx = tid + 256 * (it0 + u);
+              const int rl = idx / CPR, c = idx - rl * CPR;
+              const int wrow = rl / (HB * 32), within = rl - wrow * (HB * 32);
+              const int64_t tok = my_row0 + wrow * (BM / 2) + half * (HB * 32) + within;
+              const float4 v = *reinterpret_cast<const float4 *>(smem + rl * C::PITCH_F32 + c * 16);
+              float4 gt = make_float4(1.f, 1.f, 1.f, 1.f);
+              if (p.gate_tab) {
+                const int64_t ds = tok - sample1_tok;   // >= 0: second sample of the tile (or beyond)
+                if (ds < p.tokens_per_sample) {
+                  gt = *reinterpret_cast<const float4 *>(smem_gate + (ds >= 0 ? BN : 0) + c * 4);
+                } else {   // a tile over more than two samples (tiny shapes only): fetch the gate directly
+                  const int f = my_col0 + c * 4;
+                  gt = *reinterpret_cast<const float4 *>(p.gate_tab + f);
+                  if (p.gate_c6) {
+                    const float4 gc = *reinterpret_cast<const float4 *>(
+                        p.gate_c6 + (tok / p.tokens_per_sample) * p.gate_c6_stride + f);
+                    gt.x += gc.x; gt.y += gc.y; gt.z += gc.z; gt.w += gc.w;
+                  }
+                }
               }
-              v.x *= gt.x; v.y *= gt.y; v.z *= gt.z; v.w *= gt.w;
-            }
-            r.x += v.x; r.y += v.y; r.z += v.z; r.w += v.w;
-            *rp = r;
-            if (p.out) {
-              bf16x4 o;
-              o[0] = (bf16_t)r.x; o[1] = (bf16_t)r.y; o[2] = (bf16_t)r.z; o[3] = (bf16_t)r.w;
-              *reinterpret_cast<bf16x4 *>(p.out + tok * p.ld_out + f) = o;
+              float4 r = xr[u];
+              r.x += v.x * gt.x; r.y += v.y * gt.y; r.z += v.z * gt.z; r.w += v.w * gt.w;
+              *reinterpret_cast<float4 *>(p.resid + off[u]) = r;
+              if (p.out) {
+                bf16x4 o;
+                o[0] = (bf16_t)r.x; o[1] = (bf16_t)r.y; o[2] = (bf16_t)r.z; o[3] = (bf16_t)r.w;
+                *reinterpret_cast<bf16x4 *>(p.out + tok * p.ld_out + my_col0 + c * 4) = o;
+              }
             }
           }
         }
@@ -406,6 +463,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
   }
 #undef GEMM_SET_TILE
 #undef GEMM_BIAS_LOAD
+#undef GEMM_GATE_LOAD
 #undef GEMM_G_LOAD
 #undef GEMM_G_LOAD_FULL
 #undef GEMM_S_STORE
@@ -446,11 +504,11 @@ int launch_one(const GemmParams &p0, hipStream_t s) {
   static bool attr_set = false;  // benign race: the attribute is idempotent
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<BM, BN, EPI>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM + 2 * BN * 4);
     if (e != hipSuccess) return ddit::hip_fail(e, "gemm hipFuncSetAttribute");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_gemm_bf16<BM, BN, EPI>), dim3((unsigned)grid), dim3(256), C::SMEM, s, p);
+  hipLaunchKernelGGL((k_gemm_bf16<BM, BN, EPI>), dim3((unsigned)grid), dim3(256), C::SMEM + 2 * BN * 4, s, p);
   return ddit::hip_fail(hipGetLastError(), "gemm launch");
 }
 
