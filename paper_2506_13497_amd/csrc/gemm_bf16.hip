@@ -48,7 +48,7 @@ struct GemmParams {
   const float *gate_tab;
   const float *gate_c6; int64_t gate_c6_stride;
   int64_t tokens_per_sample;
-  int tiles_n; int total_tiles; int rounds;
+  int tiles_m; int tiles_n; int group_w; int total_tiles; int rounds;
 };
 
 __device__ __forceinline__ float gelu_tanh_f(float u) {
@@ -84,6 +84,31 @@ __device__ __forceinline__ void sched_interleave() {
   }
 }
 
+// Order of the output tiles.  Tiles are enumerated in groups of `group_w` out-feature tiles and,
+// inside a group, token-panel major; that sequence is cut into 8 contiguous parts, one per XCD
+// (workgroups are dealt round-robin to the XCDs, each with its own L2), and in every round the
+// workgroups of an XCD take the next consecutive tiles of its part.  An XCD therefore works for
+// many rounds on the same few W tiles (they stay in its L2) while it streams token panels of u,
+// each of which is shared by the group_w workgroups next to each other.
+__device__ __forceinline__ int tile_sequence_index(const GemmParams &p, int round) {
+  const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3, per = gridDim.x >> 3;
+  const int q8 = p.total_tiles >> 3, r8 = p.total_tiles & 7;
+  const int cnt = q8 + (xcd < r8 ? 1 : 0);
+  const int idx = round * per + loc;
+  if (idx >= cnt) return -1;
+  return xcd * q8 + (xcd < r8 ? xcd : r8) + idx;
+}
+__device__ __forceinline__ void decode_tile(const GemmParams &p, int L, int &tile_m, int &tile_n) {
+  const int gsz = p.tiles_m * p.group_w;
+  int g = L / gsz;
+  const int full = p.tiles_n / p.group_w;
+  int bw = p.group_w;
+  if (g >= full) { g = full; bw = p.tiles_n - full * p.group_w; }
+  const int r = L - g * gsz;
+  tile_m = r / bw;
+  tile_n = g * p.group_w + (r - tile_m * bw);
+}
+
 template <int BM, int BN>
 struct GemmCfg {
   static constexpr int STAGE = (BM + BN) * ROW_BYTES;
@@ -95,6 +120,135 @@ struct GemmCfg {
   static constexpr int SMEM = MAIN_BYTES > EPI_BF16_BYTES ? (MAIN_BYTES > EPI_F32_BYTES ? MAIN_BYTES : EPI_F32_BYTES)
                                                           : (EPI_BF16_BYTES > EPI_F32_BYTES ? EPI_BF16_BYTES : EPI_F32_BYTES);
 };
+
+// Epilogue of one output tile.  acc[a][b][4g+e] = C[token tb + l32][feature fb + 8g + 4 lh + e]
+// (bias already inside).  The accumulators are staged through LDS (`smem`, free once the k loop is
+// done; the caller guarantees no read of it is pending) so that global memory sees whole-row pieces.
+// Ends with every thread past a barrier after its last read of the staging area when EPI == 2;
+// for the bf16 epilogues the caller places that barrier before reusing `smem`.
+template <int BM, int BN, int EPI>
+__device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BN / 64][BM / 64], unsigned char *smem,
+                                              const float *smem_gate, const GemmParams &p, int64_t my_row0,
+                                              int my_col0, int64_t my_sample0, int tid, int wm, int wn, int l32,
+                                              int lh) {
+  using C = GemmCfg<BM, BN>;
+  constexpr int TM = BM / 64;
+  constexpr int TN = BN / 64;
+  if constexpr (EPI != 2) {
+    // bias (+ GELU), round to bf16, stage the whole BM x BN tile, then store whole rows
+#pragma unroll
+    for (int a = 0; a < TN; ++a) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int fl = wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;   // feature inside the tile
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+          float v0 = acc[a][b][4 * g + 0], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
+                v3 = acc[a][b][4 * g + 3];
+          if (EPI == 1) {
+            v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
+          }
+          bf16x4 o;
+          o[0] = (bf16_t)v0; o[1] = (bf16_t)v1; o[2] = (bf16_t)v2; o[3] = (bf16_t)v3;
+          const int rl = wm * (BM / 2) + b * 32 + l32;             // token inside the tile
+          *reinterpret_cast<bf16x4 *>(smem + rl * C::PITCH_BF16 + fl * 2) = o;
+        }
+      }
+    }
+    lds_barrier();
+    constexpr int CPR = BN / 8;   // 16-byte chunks per tile row
+#pragma unroll 8
+    for (int idx = tid; idx < BM * CPR; idx += 256) {
+      const int rl = idx / CPR, c = idx - rl * CPR;
+      const int64_t tok = my_row0 + rl;
+      const int f = my_col0 + c * 8;
+      if (tok < p.N && f < p.n)
+        *reinterpret_cast<uint4 *>(p.out + tok * p.ld_out + f) =
+            *reinterpret_cast<const uint4 *>(smem + rl * C::PITCH_BF16 + c * 16);
+    }
+  } else {
+    // gated residual: the raw accumulators are staged in two halves of BM/2 rows (an fp32
+    // tile does not fit LDS in one piece); bias, gate and the update of x happen on the way
+    // out, on whole-row pieces
+    constexpr int HB = TM / 2;        // token tiles per wave per half
+    constexpr int HROWS = BM / 2;     // rows per half: wave-row wm owns HB*32 of them
+    constexpr int CPR = BN / 4;       // float4 chunks per tile row
+    const int64_t sample1_tok = (my_sample0 + 1) * p.tokens_per_sample;   // first token of the tile's second sample
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
+      for (int bb = 0; bb < HB; ++bb) {
+        const int b = half * HB + bb;
+        const int rl = wm * (HB * 32) + bb * 32 + l32;             // row inside the half
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int fl = wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;
+            *reinterpret_cast<float4 *>(smem + rl * C::PITCH_F32 + fl * 4) =
+                make_float4(acc[a][b][4 * g + 0], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]);
+          }
+      }
+      lds_barrier();
+      // Loads of x are batched ahead of the stores (the compiler must assume that a store to
+      // the stream may alias a later load from it, so it would serialise them one by one).
+      constexpr int ITERS = HROWS * CPR / 256;
+      constexpr int UB = ITERS % 8 == 0 ? 8 : (ITERS % 6 == 0 ? 6 : (ITERS % 4 == 0 ? 4 : 1));
+      static_assert(HROWS * CPR % 256 == 0, "row pieces must divide evenly over the threads");
+#pragma unroll 1
+      for (int it0 = 0; it0 < ITERS; it0 += UB) {
+        float4 xr[UB];
+        int64_t off[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+          const int idx = tid + 256 * (it0 + u);
+          const int rl = idx / CPR, c = idx - rl * CPR;
+          const int wrow = rl / (HB * 32), within = rl - wrow * (HB * 32);
+          const int64_t tok = my_row0 + wrow * (BM / 2) + half * (HB * 32) + within;
+          const int f = my_col0 + c * 4;
+          const bool ok = tok < p.N && f < p.n;
+          off[u] = ok ? tok * (int64_t)p.n + f : -1;
+          xr[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (ok) xr[u] = *reinterpret_cast<const float4 *>(p.resid + off[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+          if (off[u] >= 0) {
+            const int idx = tid + 256 * (it0 + u);
+            const int rl = idx / CPR, c = idx - rl * CPR;
+            const int wrow = rl / (HB * 32), within = rl - wrow * (HB * 32);
+            const int64_t tok = my_row0 + wrow * (BM / 2) + half * (HB * 32) + within;
+            const float4 v = *reinterpret_cast<const float4 *>(smem + rl * C::PITCH_F32 + c * 16);
+            float4 gt = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (p.gate_tab) {
+              const int64_t ds = tok - sample1_tok;   // >= 0: second sample of the tile (or beyond)
+              if (ds < p.tokens_per_sample) {
+                gt = *reinterpret_cast<const float4 *>(smem_gate + (ds >= 0 ? BN : 0) + c * 4);
+              } else {   // a tile over more than two samples (tiny shapes only): fetch the gate directly
+                const int f = my_col0 + c * 4;
+                gt = *reinterpret_cast<const float4 *>(p.gate_tab + f);
+                if (p.gate_c6) {
+                  const float4 gc = *reinterpret_cast<const float4 *>(
+                      p.gate_c6 + (tok / p.tokens_per_sample) * p.gate_c6_stride + f);
+                  gt.x += gc.x; gt.y += gc.y; gt.z += gc.z; gt.w += gc.w;
+                }
+              }
+            }
+            float4 r = xr[u];
+            r.x += v.x * gt.x; r.y += v.y * gt.y; r.z += v.z * gt.z; r.w += v.w * gt.w;
+            *reinterpret_cast<float4 *>(p.resid + off[u]) = r;
+            if (p.out) {
+              bf16x4 o;
+              o[0] = (bf16_t)r.x; o[1] = (bf16_t)r.y; o[2] = (bf16_t)r.z; o[3] = (bf16_t)r.w;
+              *reinterpret_cast<bf16x4 *>(p.out + tok * p.ld_out + my_col0 + c * 4) = o;
+            }
+          }
+        }
+      }
+      lds_barrier();   // the staging area is rewritten by the next half / the next tile's prologue
+    }
+  }
+}
 
 template <int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
@@ -126,14 +280,9 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
   const int nk = (p.k + BK - 1) / BK;
   const int n_steady = (p.k / BK) - 2;  // k-steps kt with kt+2 a full step
 
-  // tile of this workgroup in round r: the 32 workgroups of an XCD take 32 consecutive tiles
-  const int G = gridDim.x;
-  const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
-  const int per_xcd = (G + 7) >> 3;
-  auto tile_of = [&](int r) -> int {
-    const int t = r * G + xcd * per_xcd + loc;
-    // G is a multiple of 8 whenever there is more than one round, so this is a bijection
-    return t;
+  auto tile_of = [&](int r) -> int {   // position in the tile sequence, or total_tiles when there is none
+    const int t = tile_sequence_index(p, r);
+    return t < 0 ? p.total_tiles : t;
   };
 
   int u_off[U_CH];   // element offsets; the host checks that they fit 31 bits
@@ -150,8 +299,8 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
 
 #define GEMM_SET_TILE(TILE)                                                                        \
   do {                                                                                             \
-    const int tile_m_ = (TILE) / p.tiles_n;                                                        \
-    const int tile_n_ = (TILE) - tile_m_ * p.tiles_n;                                              \
+    int tile_m_, tile_n_;                                                                          \
+    decode_tile(p, (TILE), tile_m_, tile_n_);                                                      \
     row0 = (int64_t)tile_m_ * BM;                                                                  \
     col0 = tile_n_ * BN;                                                                           \
     _Pragma("unroll") for (int i = 0; i < U_CH; ++i) {                                             \
@@ -343,120 +492,7 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
       GEMM_G_LOAD(0);
     }
 
-    if constexpr (EPI != 2) {
-      // bias (+ GELU), round to bf16, stage the whole BM x BN tile, then store whole rows
-#pragma unroll
-      for (int a = 0; a < TN; ++a) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int fl = wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;   // feature inside the tile
-#pragma unroll
-          for (int b = 0; b < TM; ++b) {
-            float v0 = acc[a][b][4 * g + 0], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
-                  v3 = acc[a][b][4 * g + 3];
-            if (EPI == 1) {
-              v0 = gelu_tanh_f(v0); v1 = gelu_tanh_f(v1); v2 = gelu_tanh_f(v2); v3 = gelu_tanh_f(v3);
-            }
-            bf16x4 o;
-            o[0] = (bf16_t)v0; o[1] = (bf16_t)v1; o[2] = (bf16_t)v2; o[3] = (bf16_t)v3;
-            const int rl = wm * (BM / 2) + b * 32 + l32;             // token inside the tile
-            *reinterpret_cast<bf16x4 *>(smem + rl * C::PITCH_BF16 + fl * 2) = o;
-          }
-        }
-      }
-      lds_barrier();
-      constexpr int CPR = BN / 8;   // 16-byte chunks per tile row
-#pragma unroll 8
-      for (int idx = tid; idx < BM * CPR; idx += 256) {
-        const int rl = idx / CPR, c = idx - rl * CPR;
-        const int64_t tok = my_row0 + rl;
-        const int f = my_col0 + c * 8;
-        if (tok < p.N && f < p.n)
-          *reinterpret_cast<uint4 *>(p.out + tok * p.ld_out + f) =
-              *reinterpret_cast<const uint4 *>(smem + rl * C::PITCH_BF16 + c * 16);
-      }
-    } else {
-      // gated residual: the raw accumulators are staged in two halves of BM/2 rows (an fp32
-      // tile does not fit LDS in one piece); bias, gate and the update of x happen on the way
-      // out, on whole-row pieces
-      constexpr int HB = TM / 2;        // token tiles per wave per half
-      constexpr int HROWS = BM / 2;     // rows per half: wave-row wm owns HB*32 of them
-      constexpr int CPR = BN / 4;       // float4 chunks per tile row
-      const int64_t sample1_tok = (my_sample0 + 1) * p.tokens_per_sample;   // first token of the tile's second sample
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-#pragma unroll
-        for (int bb = 0; bb < HB; ++bb) {
-          const int b = half * HB + bb;
-          const int rl = wm * (HB * 32) + bb * 32 + l32;             // row inside the half
-#pragma unroll
-          for (int a = 0; a < TN; ++a)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-              const int fl = wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;
-              *reinterpret_cast<float4 *>(smem + rl * C::PITCH_F32 + fl * 4) =
-                  make_float4(acc[a][b][4 * g + 0], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]);
-            }
-        }
-        lds_barrier();
-        // Loads of x are batched ahead of the stores (the compiler must assume that a store to
-        // the stream may alias a later load from it, so it would serialise them one by one).
-        constexpr int ITERS = HROWS * CPR / 256;
-        constexpr int UB = ITERS % 8 == 0 ? 8 : (ITERS % 6 == 0 ? 6 : (ITERS % 4 == 0 ? 4 : 1));
-        static_assert(HROWS * CPR % 256 == 0, "row pieces must divide evenly over the threads");
-#pragma unroll 1
-        for (int it0 = 0; it0 < ITERS; it0 += UB) {
-          float4 xr[UB];
-          int64_t off[UB];
-#pragma unroll
-          for (int u = 0; u < UB; ++u) {
-            const int idx = tid + 256 * (it0 + u);
-            const int rl = idx / CPR, c = idx - rl * CPR;
-            const int wrow = rl / (HB * 32), within = rl - wrow * (HB * 32);
-            const int64_t tok = my_row0 + wrow * (BM / 2) + half * (HB * 32) + within;
-            const int f = my_col0 + c * 4;
-            const bool ok = tok < p.N && f < p.n;
-            off[u] = ok ? tok * (int64_t)p.n + f : -1;
-            xr[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ok) xr[u] = *reinterpret_cast<const float4 *>(p.resid + off[u]);
-          }
-#pragma unroll
-          for (int u = 0; u < UB; ++u) {
-            if (off[u] >= 0) {
-              const int idx = tid + 256 * (it0 + u);
-              const int rl = idx / CPR, c = idx - rl * CPR;
-              const int wrow = rl / (HB * 32), within = rl - wrow * (HB * 32);
-              const int64_t tok = my_row0 + wrow * (BM / 2) + half * (HB * 32) + within;
-              const float4 v = *reinterpret_cast<const float4 *>(smem + rl * C::PITCH_F32 + c * 16);
-              float4 gt = make_float4(1.f, 1.f, 1.f, 1.f);
-              if (p.gate_tab) {
-                const int64_t ds = tok - sample1_tok;   // >= 0: second sample of the tile (or beyond)
-                if (ds < p.tokens_per_sample) {
-                  gt = *reinterpret_cast<const float4 *>(smem_gate + (ds >= 0 ? BN : 0) + c * 4);
-                } else {   // a tile over more than two samples (tiny shapes only): fetch the gate directly
-                  const int f = my_col0 + c * 4;
-                  gt = *reinterpret_cast<const float4 *>(p.gate_tab + f);
-                  if (p.gate_c6) {
-                    const float4 gc = *reinterpret_cast<const float4 *>(
-                        p.gate_c6 + (tok / p.tokens_per_sample) * p.gate_c6_stride + f);
-                    gt.x += gc.x; gt.y += gc.y; gt.z += gc.z; gt.w += gc.w;
-                  }
-                }
-              }
-              float4 r = xr[u];
-              r.x += v.x * gt.x; r.y += v.y * gt.y; r.z += v.z * gt.z; r.w += v.w * gt.w;
-              *reinterpret_cast<float4 *>(p.resid + off[u]) = r;
-              if (p.out) {
-                bf16x4 o;
-                o[0] = (bf16_t)r.x; o[1] = (bf16_t)r.y; o[2] = (bf16_t)r.z; o[3] = (bf16_t)r.w;
-                *reinterpret_cast<bf16x4 *>(p.out + tok * p.ld_out + my_col0 + c * 4) = o;
-              }
-            }
-          }
-        }
-        lds_barrier();   // the staging area is rewritten by the next half / the next tile's prologue
-      }
-    }
+    gemm_epilogue<BM, BN, EPI>(acc, smem, smem_gate, p, my_row0, my_col0, my_sample0, tid, wm, wn, l32, lh);
     if (!more) break;
     if constexpr (EPI != 2) lds_barrier();   // staged rows are read by other waves until here
     tile = next_tile;
@@ -471,6 +507,197 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
 #undef GEMM_MFMAS
 }
 
+// ---------------------------------------------------------------------------------------------
+// Direct-to-LDS variant (k a multiple of 32).  Operand tiles go global -> LDS with 16-byte
+// global_load_lds: no staging registers, no ds_write, and the loads of k-step i+3 are in flight
+// while k-step i is multiplied (four LDS stages of (BM+BN) rows x 64 B).  A wave-wide load places
+// lane l's piece at LDS base + 16 l, i.e. 16 consecutive 64-byte rows; the XOR swizzle that keeps
+// the fragment reads conflict-free (chunk slot = chunk ^ ((row >> 1) & 3)) is therefore applied
+// to the GLOBAL address each lane fetches from.  Completion is tracked with the vector-memory
+// counter, which retires in order: before the barrier of k-step i each wave waits until at most
+// the loads of k-steps i+2 and i+3 are outstanding, so past the barrier stage i+1 is complete.
+// ---------------------------------------------------------------------------------------------
+constexpr int DL_BK = 32;
+constexpr int DL_ROW = 64;   // bytes per LDS row
+constexpr int DL_NS = 4;     // stages
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+typedef __attribute__((address_space(1))) const void *gbl_ptr_t;
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else if constexpr (N == 7) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
+  else if constexpr (N == 14) asm volatile("s_waitcnt vmcnt(14)" ::: "memory");
+  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else static_assert(N == 0, "unsupported count");
+}
+
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_dl(GemmParams p) {
+  using C = GemmCfg<BM, BN>;
+  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int STAGE = (BM + BN) * DL_ROW;
+  constexpr int NI = (BM + BN) / 16;   // wave-wide loads per k-step (16 rows each)
+  constexpr int NJ = NI / 4;           // per wave
+  constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
+  static_assert(NI % 4 == 0, "loads must divide over the four waves");
+  static_assert(DL_NS * STAGE <= C::SMEM, "stages must fit the shared allocation");
+  static_assert(NJ == 7 || NJ == 4, "wait_vmcnt covers these counts");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  float *smem_gate = reinterpret_cast<float *>(smem + C::SMEM);
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int nk = p.k / DL_BK;
+
+  // fragment reads: row (tile*32 + l32) of 64 B, chunk (2 kk + lh) at slot chunk ^ ((row >> 1) & 3)
+  const int frag_u = (wm * (BM / 2) + l32) * DL_ROW;
+  const int frag_w = BM * DL_ROW + (wn * (BN / 2) + l32) * DL_ROW;
+  int coff[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) coff[kk] = ((kk * 2 + lh) ^ ((l32 >> 1) & 3)) << 4;
+  // loads: instruction g = wave*NJ + j covers tile rows 16 g .. 16 g + 15; this lane: row lane/4, slot lane%4
+  const int ld_row = lane >> 2;
+  const int ld_chunk = ((lane & 3) ^ ((ld_row >> 1) & 3)) * 8;   // element offset of the global chunk to fetch
+
+  int src_off[NJ];   // element offset of this lane's piece at k = 0 (u or W, by instruction)
+
+#define DL_ISSUE(KT)                                                                               \
+  do {                                                                                             \
+    const int k0_ = (KT) * DL_BK;                                                                  \
+    unsigned char *sb_ = smem + ((KT) & (DL_NS - 1)) * STAGE + wave * NJ * 1024;                   \
+    _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                               \
+      const bf16_t *src_ = ((wave * NJ + j) * 16 < BM ? p.u : p.W) + src_off[j] + k0_;             \
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)src_, (lds_ptr_t)(sb_ + j * 1024), 16, 0, 0);    \
+    }                                                                                              \
+  } while (0)
+
+#define DL_READ_FRAGS(BUF, KT, KK)                                                                 \
+  do {                                                                                             \
+    const unsigned char *sb_ = smem + ((KT) & (DL_NS - 1)) * STAGE + coff[KK];                     \
+    _Pragma("unroll") for (int b = 0; b < TM; ++b)                                                 \
+        uf[BUF][b] = *reinterpret_cast<const bf16x8 *>(sb_ + frag_u + b * 32 * DL_ROW);            \
+    _Pragma("unroll") for (int a = 0; a < TN; ++a)                                                 \
+        wf[BUF][a] = *reinterpret_cast<const bf16x8 *>(sb_ + frag_w + a * 32 * DL_ROW);            \
+  } while (0)
+
+#define DL_MFMAS(BUF)                                                                              \
+  do {                                                                                             \
+    _Pragma("unroll") for (int a = 0; a < TN; ++a)                                                 \
+        _Pragma("unroll") for (int b = 0; b < TM; ++b)                                             \
+            acc[a][b] = mfma32(wf[BUF][a], uf[BUF][b], acc[a][b]);                                 \
+  } while (0)
+
+  for (int round = 0; round < p.rounds; ++round) {
+    const int tile = tile_sequence_index(p, round);
+    if (tile < 0) break;
+    int tile_m, tile_n;
+    decode_tile(p, tile, tile_m, tile_n);
+    const int64_t row0 = (int64_t)tile_m * BM;
+    const int col0 = tile_n * BN;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int R = (wave * NJ + j) * 16 + ld_row;
+      if (R < BM) {
+        int64_t t = row0 + R;
+        if (t > p.N - 1) t = p.N - 1;           // overhanging rows re-read the last row; never stored
+        src_off[j] = (int)(t * p.ld_u) + ld_chunk;
+      } else {
+        int f = col0 + R - BM;
+        if (f > p.n - 1) f = p.n - 1;
+        src_off[j] = f * p.k + ld_chunk;
+      }
+    }
+    // bias and gate first: the memory counter retires in order, so what is needed first is issued first
+    bf16x4 bias_r[TN][4];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bias_r[a][g][e] = (bf16_t)0.f;
+        if (p.bias) {
+          int f = col0 + wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;
+          if (f > p.n - 4) f = p.n - 4;
+          bias_r[a][g] = *reinterpret_cast<const bf16x4 *>(p.bias + f);
+        }
+      }
+    int64_t sample0 = 0;
+    if (EPI == 2 && p.gate_tab) {
+      sample0 = row0 / p.tokens_per_sample;
+      if (tid < 2 * (BN / 4)) {
+        const int which = tid / (BN / 4), c = tid - which * (BN / 4);
+        int f = col0 + 4 * c;
+        if (f > p.n - 4) f = p.n - 4;
+        float4 gt = *reinterpret_cast<const float4 *>(p.gate_tab + f);
+        if (p.gate_c6) {
+          int64_t smp = sample0 + which;
+          const int64_t last = (p.N - 1) / p.tokens_per_sample;
+          if (smp > last) smp = last;
+          const float4 gc = *reinterpret_cast<const float4 *>(p.gate_c6 + smp * p.gate_c6_stride + f);
+          gt.x += gc.x; gt.y += gc.y; gt.z += gc.z; gt.w += gc.w;
+        }
+        *reinterpret_cast<float4 *>(smem_gate + tid * 4) = gt;
+      }
+    }
+    DL_ISSUE(0);
+    if (nk > 1) DL_ISSUE(1);
+    if (nk > 2) DL_ISSUE(2);
+
+    floatx16 acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+      for (int b = 0; b < TM; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[a][b][e] = (float)bias_r[a][e >> 2][e & 3];
+
+    if (nk > 2) wait_vmcnt<2 * NJ>();
+    else if (nk > 1) wait_vmcnt<NJ>();
+    else wait_vmcnt<0>();
+    lds_barrier();
+
+    bf16x8 uf[2][TM], wf[2][TN];
+    DL_READ_FRAGS(0, 0, 0);
+    int kt = 0;
+    // ---- steady state: k-steps kt+1 .. kt+3 exist; no branches, issue order pinned
+    for (; kt + 3 < nk; ++kt) {
+      DL_READ_FRAGS(1, kt, 1);
+      DL_ISSUE(kt + 3);
+      DL_MFMAS(0);
+      __builtin_amdgcn_sched_group_barrier(SG_DS_RD, NFRAG, 0);
+      sched_interleave<SG_VMEM_RD, 0, NMFMA, NJ>();
+      __builtin_amdgcn_sched_barrier(0);
+      wait_vmcnt<2 * NJ>();   // k-step kt+1 has landed (this wave's part)
+      lds_barrier();          // ... everyone's part; and every wave is done reading stage kt
+      DL_READ_FRAGS(0, kt + 1, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      DL_MFMAS(1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // ---- last k-steps
+    for (; kt < nk; ++kt) {
+      DL_READ_FRAGS(1, kt, 1);
+      DL_MFMAS(0);
+      if (kt + 2 < nk) wait_vmcnt<NJ>();
+      else wait_vmcnt<0>();
+      lds_barrier();
+      if (kt + 1 < nk) DL_READ_FRAGS(0, kt + 1, 0);
+      DL_MFMAS(1);
+    }
+    // every wave is past the last barrier of the k loop: no LDS read of the stages is pending
+    gemm_epilogue<BM, BN, EPI>(acc, smem, smem_gate, p, row0, col0, sample0, tid, wm, wn, l32, lh);
+    if constexpr (EPI != 2) lds_barrier();   // staged rows are read by other waves until here
+  }
+#undef DL_ISSUE
+#undef DL_READ_FRAGS
+#undef DL_MFMAS
+}
+
 int num_cus() {
   static int cus = 0;
   if (cus == 0) {
@@ -483,12 +710,16 @@ int num_cus() {
   return cus;
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, bool DIRECT>
 int launch_one(const GemmParams &p0, hipStream_t s) {
   using C = GemmCfg<BM, BN>;
   GemmParams p = p0;
   const int64_t tiles_m = (p.N + BM - 1) / BM;
+  p.tiles_m = (int)tiles_m;
   p.tiles_n = (p.n + BN - 1) / BN;
+  // width of an out-feature group: at most 8 tiles, as even as the tile count allows
+  const int n_groups = (p.tiles_n + 7) / 8;
+  p.group_w = (p.tiles_n + n_groups - 1) / n_groups;
   const int64_t total = tiles_m * p.tiles_n;
   if (total > (int64_t)1 << 30) {
     ddit::set_error("linear: %lld output tiles: too many", (long long)total);
@@ -500,15 +731,19 @@ int launch_one(const GemmParams &p0, hipStream_t s) {
   int grid = num_cus() & ~7;
   if (grid < 8) grid = 8;
   if (total <= grid) grid = (int)((total + 7) & ~(int64_t)7);
-  p.rounds = (int)((total + grid - 1) / grid);
+  p.rounds = (int)(((total + 7) / 8 + grid / 8 - 1) / (grid / 8));
   static bool attr_set = false;  // benign race: the attribute is idempotent
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<BM, BN, EPI>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM + 2 * BN * 4);
+    const void *fn = DIRECT ? reinterpret_cast<const void *>(&k_gemm_dl<BM, BN, EPI>)
+                            : reinterpret_cast<const void *>(&k_gemm_bf16<BM, BN, EPI>);
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM + 2 * BN * 4);
     if (e != hipSuccess) return ddit::hip_fail(e, "gemm hipFuncSetAttribute");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_gemm_bf16<BM, BN, EPI>), dim3((unsigned)grid), dim3(256), C::SMEM + 2 * BN * 4, s, p);
+  if (DIRECT)
+    hipLaunchKernelGGL((k_gemm_dl<BM, BN, EPI>), dim3((unsigned)grid), dim3(256), C::SMEM + 2 * BN * 4, s, p);
+  else
+    hipLaunchKernelGGL((k_gemm_bf16<BM, BN, EPI>), dim3((unsigned)grid), dim3(256), C::SMEM + 2 * BN * 4, s, p);
   return ddit::hip_fail(hipGetLastError(), "gemm launch");
 }
 
@@ -517,8 +752,10 @@ int launch_epi(const GemmParams &p, hipStream_t s) {
   // 192-wide feature tiles divide 1152, 3456, 4608 and 2304 exactly; narrow outputs and
   // short token counts take the smaller tile so more than a handful of CUs get work.
   const int64_t big_tiles = ((p.N + 255) / 256) * ((p.n + 191) / 192);
-  if (big_tiles >= 128 && (p.n % 192 == 0 || p.n > 1024)) return launch_one<256, 192, EPI>(p, s);
-  return launch_one<128, 128, EPI>(p, s);
+  const bool big = big_tiles >= 128 && (p.n % 192 == 0 || p.n > 1024);
+  // the direct-to-LDS kernel cannot zero-fill a k tail
+  if (p.k % DL_BK == 0) return big ? launch_one<256, 192, EPI, true>(p, s) : launch_one<128, 128, EPI, true>(p, s);
+  return big ? launch_one<256, 192, EPI, false>(p, s) : launch_one<128, 128, EPI, false>(p, s);
 }
 
 }  // namespace
@@ -544,7 +781,7 @@ int launch_gemm(int epilogue, const GemmArgs &a, hipStream_t s) {
   p.resid = a.resid;
   p.gate_tab = a.gate_tab; p.gate_c6 = a.gate_c6; p.gate_c6_stride = a.gate_c6_stride;
   p.tokens_per_sample = a.tokens_per_sample > 0 ? a.tokens_per_sample : 1;
-  p.tiles_n = 0; p.total_tiles = 0; p.rounds = 0;
+  p.tiles_m = 0; p.tiles_n = 0; p.group_w = 1; p.total_tiles = 0; p.rounds = 0;
   switch (epilogue) {
     case 0: return launch_epi<0>(p, s);
     case 1: return launch_epi<1>(p, s);
