@@ -5,38 +5,48 @@
 // (8 consecutive k per lane), so tiles go global -> LDS -> registers as 16-byte pieces
 // with no transposition anywhere.
 //
-// Tiling.  One workgroup of 4 wavefronts owns a BM x BN tile of the output (BM tokens,
-// BN out-features) and walks k in steps of 64.  The wavefronts form a 2x2 grid; each
-// owns (BM/2) x (BN/2), i.e. (BM/64)*(BN/64) MFMA tiles of 32x32 with fp32 accumulators
-// in registers.  The MFMA is issued with W as its first operand and u as its second, so
-// a lane ends up holding, for one token, 4 consecutive out-features per accumulator group.
-// LDS holds two stages of (BM + BN) rows x 128 B.  A row's eight 16-byte chunks are
-// stored at chunk position c ^ (row & 7): the ds_read_b128 of 8 consecutive rows at the
-// same k then touches all 32 banks once.
+// Tiling.  A workgroup of WGM x WGN wavefronts owns a BM x BN tile of the output (BM tokens,
+// BN out-features); a wavefront owns TM x TN MFMA tiles of 32x32 with fp32 accumulators in
+// registers.  The MFMA is issued with W as its first operand and u as its second, so a lane
+// ends up holding, for one token, 4 consecutive out-features per accumulator group.
+// The main configuration is 192 x 384 with eight wavefronts (2 x 4, each 96 x 96): the
+// accumulators fill half of the compute unit's register file.  What sets the tile size is the
+// path from L2 into the compute units: it delivers well under 100 bytes per clock to a CU, so a
+// tile has to do about 128 flop per byte fetched, which 192 x 384 does (and 384 divides the
+// model's widths 1152, 3456 and 4608).  Two wavefronts share a SIMD: one wavefront alone can draw
+// only about 30 B/clk from the LDS, less than its matrix core eats.
 //
-// Pipeline.  A k-step is four sub-steps of 16.  The fragments of sub-step s+1 are read
-// from LDS while the MFMAs of sub-step s run (register double buffer); the LDS writes of
-// k-step i+1 and the global loads of k-step i+2 are slotted between the MFMAs of
-// sub-steps 0 and 1; the last sub-step prefetches the first fragments of the next stage.
-// One barrier per k-step.  The issue order inside a sub-step is pinned with
-// sched_group_barrier, since with one wavefront per SIMD nothing else hides LDS latency.
+// Operand path.  k is walked in steps of 32.  Tiles go global -> LDS with 16-byte
+// global_load_lds: no staging registers, no ds_write, and the loads of k-step i+NS-1 are in
+// flight while k-step i is multiplied (NS LDS stages of (BM+BN) rows x 64 B).  A wave-wide
+// load places lane l's piece at LDS base + 16 l, i.e. 16 consecutive 64-byte rows.  The LDS
+// of this chip has 64 banks (256 B per clock): the four 16-byte chunks of row r are stored
+// at slot chunk ^ ((r >> 2) & 3), so the 16 lanes that a ds_read_b128 serves per clock (16
+// consecutive rows, same chunk) touch 16 different 16-byte bank groups.  Since the load
+// instruction fixes where each lane's piece lands, the swizzle is applied to the GLOBAL
+// address each lane fetches from.  The (BM+BN)/16 loads of a k-step are dealt to the wavefronts
+// round-robin; when they do not divide evenly the first wavefronts issue one more, and the k
+// loop is compiled once per count, because completion is tracked with the vector-memory
+// counter, which retires loads in order: before the barrier of k-step i each wave waits until
+// at most its loads of the later k-steps are outstanding, so past the barrier stage i+1 is
+// complete.  A k tail (k not a multiple of 32) is zero-filled by pointing the lanes past
+// the end of the row at a block of zeros.
 //
-// Persistent workgroups.  The grid is one workgroup per CU; each loops over output
-// tiles.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so in
-// every round the 32 workgroups of an XCD take 32 consecutive tiles, out-feature tile
-// fastest: they share a token panel of u.  The next tile's first global loads are issued
-// before the epilogue, and the epilogue's stores drain while the next tile is multiplied.
+// Tile order.  Persistent workgroups; see tile_sequence_index.
 //
-// Epilogue.  The accumulators are staged through LDS (free once the k loop is done) so
-// that global memory is written in whole-row pieces, 16 bytes per lane, instead of 8-byte
-// pieces scattered over 32 rows: bf16 store; GELU(tanh form) + bf16 store; gated residual
-// update of the fp32 stream (x += gate_b * (acc + bias)), optionally also storing bf16(x).
+// Epilogue.  The accumulators are staged through LDS (free once the k loop is done), 32 rows
+// per wavefront at a time, so that global memory is written in whole-row pieces, 16 bytes per
+// lane, instead of 8-byte pieces scattered over 32 rows: bf16 store; GELU(tanh form) + bf16
+// store; gated residual update of the fp32 stream (x += gate_b * (acc + bias)), optionally
+// also storing bf16(x).
 #include "ddit_common.hpp"
 
 namespace {
 
-constexpr int BK = 64;          // k per pipeline step (bf16 elements); one LDS row = 128 B
-constexpr int ROW_BYTES = 128;
+constexpr int BK = 32;        // k per pipeline step (bf16 elements)
+constexpr int ROW = 64;       // bytes per LDS row
+
+__device__ __attribute__((aligned(16))) const unsigned int k_zero_block[4] = {0u, 0u, 0u, 0u};
 
 struct GemmParams {
   const bf16_t *u; int64_t ld_u;
@@ -60,18 +70,53 @@ __device__ __forceinline__ float gelu_tanh_f(float u) {
 }
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for the
-// epilogue's global stores of the previous tile to be acknowledged, which is exactly the
-// overlap the persistent loop is after; nothing in this kernel communicates through global
-// memory inside a workgroup.
+// epilogue's global stores of the previous tile to be acknowledged; nothing in this kernel
+// communicates through global memory inside a workgroup.
 __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// 16-byte LDS reads that the compiler does not see as LDS reads.  It guards every LDS read it
+// knows of with a wait for ALL outstanding vector-memory operations (it cannot tell the
+// direct-to-LDS loads from stores), which in the epilogues would make each read wait for the round
+// trip of the stores issued just before it.  The epilogues read only what the workgroup itself
+// staged behind a barrier, so no vector-memory wait is needed there.
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ unsigned lds_offset(const void *p) {
+  return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+__device__ __forceinline__ void lds_read2_b128(uintx4 (&v)[2], unsigned a0, unsigned a1) {
+  asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+               : "=&v"(v[0]), "=&v"(v[1])
+               : "v"(a0), "v"(a1)
+               : "memory");
+}
+__device__ __forceinline__ void lds_read3_b128(uintx4 (&v)[3], unsigned a0, unsigned a1, unsigned a2) {
+  asm volatile("ds_read_b128 %0, %3\n\tds_read_b128 %1, %4\n\tds_read_b128 %2, %5\n\ts_waitcnt lgkmcnt(0)"
+               : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2])
+               : "v"(a0), "v"(a1), "v"(a2)
+               : "memory");
+}
+// the tile's bias for this lane: 4 consecutive features (8 bytes) at each of four 8-feature steps
+__device__ __forceinline__ void lds_read4_b64(uint2 (&v)[4], unsigned a) {
+  asm volatile(
+      "ds_read_b64 %0, %4\n\tds_read_b64 %1, %4 offset:16\n\tds_read_b64 %2, %4 offset:32\n\t"
+      "ds_read_b64 %3, %4 offset:48\n\ts_waitcnt lgkmcnt(0)"
+      : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3])
+      : "v"(a)
+      : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "the counter has 6 bits");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 // scheduling-group masks of __builtin_amdgcn_sched_group_barrier
 #define SG_MFMA 0x008
 #define SG_VMEM_RD 0x020
 #define SG_DS_RD 0x100
-#define SG_DS_WR 0x200
 
 // Issue order for one sub-step: NM MFMAs with NS instructions of class OTHER spread between them.
 template <int OTHER, int I, int NM, int NS>
@@ -109,40 +154,66 @@ __device__ __forceinline__ void decode_tile(const GemmParams &p, int L, int &til
   tile_n = g * p.group_w + (r - tile_m * bw);
 }
 
-template <int BM, int BN>
+template <int WGM, int WGN, int TM, int TN, int NS>
 struct GemmCfg {
-  static constexpr int STAGE = (BM + BN) * ROW_BYTES;
-  static constexpr int PITCH_BF16 = BN * 2 + 16;             // epilogue staging row pitches: +16 B keeps the
-  static constexpr int PITCH_F32 = BN * 4 + 16;              // 8 lanes of a 16-byte access on distinct banks
-  static constexpr int EPI_BF16_BYTES = BM * PITCH_BF16;
-  static constexpr int EPI_F32_BYTES = (BM / 2) * PITCH_F32;  // fp32 staging goes in two halves of BM/2 rows
-  static constexpr int MAIN_BYTES = 2 * STAGE;
-  static constexpr int SMEM = MAIN_BYTES > EPI_BF16_BYTES ? (MAIN_BYTES > EPI_F32_BYTES ? MAIN_BYTES : EPI_F32_BYTES)
-                                                          : (EPI_BF16_BYTES > EPI_F32_BYTES ? EPI_BF16_BYTES : EPI_F32_BYTES);
+  static constexpr int WGM_ = WGM;
+  static constexpr int NW = WGM * WGN;                       // wavefronts per workgroup
+  static constexpr int NT = 64 * NW;
+  static constexpr int BM = WGM * TM * 32;
+  static constexpr int BN = WGN * TN * 32;
+  static constexpr int STAGE = (BM + BN) * ROW;
+  static constexpr int MAIN_BYTES = NS * STAGE;
+  static constexpr int PASS_ROWS = WGM * 32;                 // rows staged per pass of the fp32 epilogue
+  static constexpr int PITCH_BF16 = BN * 2 + 16;             // epilogue staging row pitches
+  static constexpr int PITCH_F32 = BN * 4 + 16;
+  static constexpr int EPI_BYTES = PASS_ROWS * PITCH_F32;
+  static constexpr int SMEM = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+  static constexpr int GATE_BYTES = 2 * BN * 4;              // gate vectors of two samples, past the stages
+  static constexpr int BIAS_BYTES = BN * 2;                  // the tile's bias, past the gates
+  static constexpr int EXTRA_BYTES = GATE_BYTES + BIAS_BYTES;
+  // the bf16 epilogues stage one row-tile of every wavefront at a time inside the LAST TWO stages,
+  // so that the first stages can already receive the next tile's operands
+  static constexpr int EARLY_STEPS = NS - 2;                 // k-steps of the next tile fetched before the epilogue
+  static constexpr int BF16_STAGING = EARLY_STEPS * STAGE;
+  static_assert(PASS_ROWS * PITCH_BF16 <= 2 * STAGE, "a pass of the bf16 epilogue must fit two stages");
+  static_assert(BN / 8 <= 64, "one wavefront fetches the tile's bias");
+  static constexpr int NI = (BM + BN) / 16;                  // wave-wide loads per k-step (16 rows each)
+  static constexpr int NJ_LO = NI / NW;                      // loads per wavefront per k-step ...
+  static constexpr int N_HI = NI % NW;                       // ... one more for the first N_HI wavefronts
+  static constexpr int NJ_HI = NJ_LO + (N_HI ? 1 : 0);
+  static_assert(BM % 16 == 0 && BN % 16 == 0, "tile rows come in sixteens");
+  static_assert((NS - 2) * NJ_HI < 64 && NS >= 3, "pipeline depth");
 };
 
 // Epilogue of one output tile.  acc[a][b][4g+e] = C[token tb + l32][feature fb + 8g + 4 lh + e]
-// (bias already inside).  The accumulators are staged through LDS (`smem`, free once the k loop is
-// done; the caller guarantees no read of it is pending) so that global memory sees whole-row pieces.
-// Ends with every thread past a barrier after its last read of the staging area when EPI == 2;
-// for the bf16 epilogues the caller places that barrier before reusing `smem`.
-template <int BM, int BN, int EPI>
-__device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BN / 64][BM / 64], unsigned char *smem,
-                                              const float *smem_gate, const GemmParams &p, int64_t my_row0,
-                                              int my_col0, int64_t my_sample0, int tid, int wm, int wn, int l32,
-                                              int lh) {
-  using C = GemmCfg<BM, BN>;
-  constexpr int TM = BM / 64;
-  constexpr int TN = BN / 64;
+// (bias already inside).  Pass b stages accumulator row-tile b of every wavefront (32 rows per
+// wavefront row) and writes those rows out.  `smem` is free once the k loop is done; the caller
+// guarantees no read of it is pending.  Ends with every thread past a barrier after its last read
+// of the staging area.
+template <class C, int TM, int TN, int EPI>
+__device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TN][TM], unsigned char *smem, const float *smem_gate,
+                                              const GemmParams &p, int64_t my_row0, int my_col0, int64_t my_sample0,
+                                              int tid, int wm, int wn, int l32, int lh) {
+  constexpr int BN = C::BN, NT = C::NT, PR = C::PASS_ROWS;
+  const unsigned stage_base = lds_offset(smem);
+  const int rl_stage = wm * 32 + l32;   // this lane's row inside a pass
   if constexpr (EPI != 2) {
-    // bias (+ GELU), round to bf16, stage the whole BM x BN tile, then store whole rows
+    // Pass b: every wavefront stages its row-tile b (32 token rows x its features); everyone writes
+    // those WGM*32 rows out.
+    constexpr int CPR = BN / 8;   // 16-byte chunks per tile row
+    constexpr int ITERS = PR * CPR / NT;
+    static_assert(PR * CPR % NT == 0 && (ITERS == 4 || ITERS == 6), "row pieces per thread and pass");
+    constexpr int G = ITERS / 2;  // pieces per LDS read group
+    unsigned char *const stg = smem + C::BF16_STAGING;
+    const unsigned stg_base = lds_offset(stg);
 #pragma unroll
-    for (int a = 0; a < TN; ++a) {
+    for (int b = 0; b < TM; ++b) {
+      // bias is inside; (+ GELU), round to bf16, stage
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int fl = wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;   // feature inside the tile
+      for (int a = 0; a < TN; ++a)
 #pragma unroll
-        for (int b = 0; b < TM; ++b) {
+        for (int g = 0; g < 4; ++g) {
+          const int fl = wn * (TN * 32) + a * 32 + 8 * g + 4 * lh;   // feature inside the tile
           float v0 = acc[a][b][4 * g + 0], v1 = acc[a][b][4 * g + 1], v2 = acc[a][b][4 * g + 2],
                 v3 = acc[a][b][4 * g + 3];
           if (EPI == 1) {
@@ -150,439 +221,206 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BN / 64][BM / 64],
           }
           bf16x4 o;
           o[0] = (bf16_t)v0; o[1] = (bf16_t)v1; o[2] = (bf16_t)v2; o[3] = (bf16_t)v3;
-          const int rl = wm * (BM / 2) + b * 32 + l32;             // token inside the tile
-          *reinterpret_cast<bf16x4 *>(smem + rl * C::PITCH_BF16 + fl * 2) = o;
+          *reinterpret_cast<bf16x4 *>(stg + rl_stage * C::PITCH_BF16 + fl * 2) = o;
+        }
+      lds_barrier();
+#pragma unroll
+      for (int it0 = 0; it0 < ITERS; it0 += G) {
+        uintx4 piece[G];
+        unsigned la[G];
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          const int idx = tid + NT * (it0 + j);
+          const int rl = idx / CPR, c = idx - rl * CPR;
+          la[j] = stg_base + rl * C::PITCH_BF16 + c * 16;
+        }
+        if constexpr (G == 2) lds_read2_b128(piece, la[0], la[1]);
+        else lds_read3_b128(piece, la[0], la[1], la[2]);
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          const int idx = tid + NT * (it0 + j);
+          const int rl = idx / CPR, c = idx - rl * CPR;          // rl = 32 * wave-row + row
+          const int64_t tok = my_row0 + (rl >> 5) * (TM * 32) + b * 32 + (rl & 31);
+          const int f = my_col0 + c * 8;
+          if (tok < p.N && f < p.n) *reinterpret_cast<uintx4 *>(p.out + tok * p.ld_out + f) = piece[j];
         }
       }
-    }
-    lds_barrier();
-    constexpr int CPR = BN / 8;   // 16-byte chunks per tile row
-#pragma unroll 8
-    for (int idx = tid; idx < BM * CPR; idx += 256) {
-      const int rl = idx / CPR, c = idx - rl * CPR;
-      const int64_t tok = my_row0 + rl;
-      const int f = my_col0 + c * 8;
-      if (tok < p.N && f < p.n)
-        *reinterpret_cast<uint4 *>(p.out + tok * p.ld_out + f) =
-            *reinterpret_cast<const uint4 *>(smem + rl * C::PITCH_BF16 + c * 16);
+      lds_barrier();   // staged rows are read by other waves until here
     }
   } else {
-    // gated residual: the raw accumulators are staged in two halves of BM/2 rows (an fp32
-    // tile does not fit LDS in one piece); bias, gate and the update of x happen on the way
-    // out, on whole-row pieces
-    constexpr int HB = TM / 2;        // token tiles per wave per half
-    constexpr int HROWS = BM / 2;     // rows per half: wave-row wm owns HB*32 of them
+    // gated residual: gate * (acc + bias) is staged; the update of x happens on the way out, on
+    // whole-row pieces
     constexpr int CPR = BN / 4;       // float4 chunks per tile row
+    constexpr int ITERS = PR * CPR / NT;
+    static_assert(PR * CPR % NT == 0 && ITERS % 2 == 0, "row pieces must divide evenly over the threads, in pairs");
     const int64_t sample1_tok = (my_sample0 + 1) * p.tokens_per_sample;   // first token of the tile's second sample
+    float *const x_tile = p.resid + my_row0 * (int64_t)p.n + my_col0;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-#pragma unroll
-      for (int bb = 0; bb < HB; ++bb) {
-        const int b = half * HB + bb;
-        const int rl = wm * (HB * 32) + bb * 32 + l32;             // row inside the half
+    for (int b = 0; b < TM; ++b) {
+      {
+        const int64_t tok = my_row0 + wm * (TM * 32) + b * 32 + l32;
+        const int64_t ds = tok - sample1_tok;                      // >= 0: second sample of the tile (or beyond)
+        const bool far = p.gate_tab && ds >= p.tokens_per_sample;  // tile over more than two samples (tiny shapes)
+        const float *grow = smem_gate + (ds >= 0 ? BN : 0);
+        const float *gfar = nullptr;                               // this row's c6 gate vector when `far`
+        if (far && p.gate_c6) {
+          int64_t smp = my_sample0 + 1, t = sample1_tok + p.tokens_per_sample;
+          const int64_t tk = tok < p.N ? tok : p.N - 1;
+          while (t <= tk) { ++smp; t += p.tokens_per_sample; }
+          gfar = p.gate_c6 + smp * p.gate_c6_stride;
+        }
 #pragma unroll
         for (int a = 0; a < TN; ++a)
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            const int fl = wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;
-            *reinterpret_cast<float4 *>(smem + rl * C::PITCH_F32 + fl * 4) =
-                make_float4(acc[a][b][4 * g + 0], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]);
-          }
-      }
-      lds_barrier();
-      // Loads of x are batched ahead of the stores (the compiler must assume that a store to
-      // the stream may alias a later load from it, so it would serialise them one by one).
-      constexpr int ITERS = HROWS * CPR / 256;
-      constexpr int UB = ITERS % 8 == 0 ? 8 : (ITERS % 6 == 0 ? 6 : (ITERS % 4 == 0 ? 4 : 1));
-      static_assert(HROWS * CPR % 256 == 0, "row pieces must divide evenly over the threads");
-#pragma unroll 1
-      for (int it0 = 0; it0 < ITERS; it0 += UB) {
-        float4 xr[UB];
-        int64_t off[UB];
-#pragma unroll
-        for (int u = 0; u < UB; ++u) {
-          const int idx = tid + 256 * (it0 + u);
-          const int rl = idx / CPR, c = idx - rl * CPR;
-          const int wrow = rl / (HB * 32), within = rl - wrow * (HB * 32);
-          const int64_t tok = my_row0 + wrow * (BM / 2) + half * (HB * 32) + within;
-          const int f = my_col0 + c * 4;
-          const bool ok = tok < p.N && f < p.n;
-          off[u] = ok ? tok * (int64_t)p.n + f : -1;
-          xr[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (ok) xr[u] = *reinterpret_cast<const float4 *>(p.resid + off[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < UB; ++u) {
-          if (off[u] >= 0) {
-            const int idx = tid + 256 * (it0 + u);
-            const int rl = idx / CPR, c = idx - rl * CPR;
-            const int wrow = rl / (HB * 32), within = rl - wrow * (HB * 32);
-            const int64_t tok = my_row0 + wrow * (BM / 2) + half * (HB * 32) + within;
-            const float4 v = *reinterpret_cast<const float4 *>(smem + rl * C::PITCH_F32 + c * 16);
+            const int fl = wn * (TN * 32) + a * 32 + 8 * g + 4 * lh;
             float4 gt = make_float4(1.f, 1.f, 1.f, 1.f);
             if (p.gate_tab) {
-              const int64_t ds = tok - sample1_tok;   // >= 0: second sample of the tile (or beyond)
-              if (ds < p.tokens_per_sample) {
-                gt = *reinterpret_cast<const float4 *>(smem_gate + (ds >= 0 ? BN : 0) + c * 4);
-              } else {   // a tile over more than two samples (tiny shapes only): fetch the gate directly
-                const int f = my_col0 + c * 4;
+              gt = *reinterpret_cast<const float4 *>(grow + fl);
+              if (far) {
+                int f = my_col0 + fl;
+                if (f > p.n - 4) f = p.n - 4;
                 gt = *reinterpret_cast<const float4 *>(p.gate_tab + f);
-                if (p.gate_c6) {
-                  const float4 gc = *reinterpret_cast<const float4 *>(
-                      p.gate_c6 + (tok / p.tokens_per_sample) * p.gate_c6_stride + f);
+                if (gfar) {
+                  const float4 gc = *reinterpret_cast<const float4 *>(gfar + f);
                   gt.x += gc.x; gt.y += gc.y; gt.z += gc.z; gt.w += gc.w;
                 }
               }
             }
-            float4 r = xr[u];
-            r.x += v.x * gt.x; r.y += v.y * gt.y; r.z += v.z * gt.z; r.w += v.w * gt.w;
-            *reinterpret_cast<float4 *>(p.resid + off[u]) = r;
+            *reinterpret_cast<float4 *>(smem + rl_stage * C::PITCH_F32 + fl * 4) =
+                make_float4(acc[a][b][4 * g + 0] * gt.x, acc[a][b][4 * g + 1] * gt.y, acc[a][b][4 * g + 2] * gt.z,
+                            acc[a][b][4 * g + 3] * gt.w);
+            __builtin_amdgcn_sched_barrier(0);   // keeps the gate reads from piling up in registers
+          }
+      }
+      lds_barrier();
+      // update of x on whole-row pieces, a few at a time (this epilogue is not the fast path: the
+      // denoising step adds its branches in the streaming kernels instead)
+      constexpr int G = ITERS % 4 == 0 ? 4 : 2;
+#pragma unroll 1
+      for (int u0 = 0; u0 < ITERS; u0 += G) {
+        float4 xr[G];
+        int off[G];      // element offset from the tile's first element, or -1
+        uintx4 piece[G];
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          const int idx = tid + NT * (u0 + j);
+          const int rl = idx / CPR, c = idx - rl * CPR;
+          const int trow = (rl >> 5) * (TM * 32) + b * 32 + (rl & 31);   // row inside the tile
+          const bool ok = my_row0 + trow < p.N && my_col0 + c * 4 < p.n;
+          off[j] = ok ? trow * p.n + c * 4 : -1;
+          xr[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (ok) xr[j] = *reinterpret_cast<const float4 *>(x_tile + off[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < G; j += 2) {
+          uintx4 two[2];
+          unsigned la[2];
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int idx = tid + NT * (u0 + j + e);
+            const int rl = idx / CPR, c = idx - rl * CPR;
+            la[e] = stage_base + rl * C::PITCH_F32 + c * 16;
+          }
+          lds_read2_b128(two, la[0], la[1]);
+          piece[j] = two[0];
+          piece[j + 1] = two[1];
+        }
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+          if (off[j] >= 0) {
+            float4 r = xr[j];
+            r.x += __uint_as_float(piece[j][0]); r.y += __uint_as_float(piece[j][1]);
+            r.z += __uint_as_float(piece[j][2]); r.w += __uint_as_float(piece[j][3]);
+            *reinterpret_cast<float4 *>(x_tile + off[j]) = r;
             if (p.out) {
+              const int trow = off[j] / p.n;
               bf16x4 o;
               o[0] = (bf16_t)r.x; o[1] = (bf16_t)r.y; o[2] = (bf16_t)r.z; o[3] = (bf16_t)r.w;
-              *reinterpret_cast<bf16x4 *>(p.out + tok * p.ld_out + my_col0 + c * 4) = o;
+              *reinterpret_cast<bf16x4 *>(p.out + (my_row0 + trow) * p.ld_out + my_col0 + (off[j] - trow * p.n)) = o;
             }
           }
         }
       }
-      lds_barrier();   // the staging area is rewritten by the next half / the next tile's prologue
+      lds_barrier();   // the staging area is rewritten by the next pass / the next tile's loads
     }
   }
 }
-
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void k_gemm_bf16(GemmParams p) {
-  using C = GemmCfg<BM, BN>;
-  constexpr int TM = BM / 64;  // 32-token MFMA tiles per wave
-  constexpr int TN = BN / 64;  // 32-feature MFMA tiles per wave
-  constexpr int U_CH = BM * 8 / 256;  // 16-byte chunks per thread per stage
-  constexpr int W_CH = BN * 8 / 256;
-  constexpr int STAGE = C::STAGE;
-  constexpr int NFRAG = TM + TN;
-  constexpr int NMFMA = TM * TN;
-  constexpr int NST = U_CH + W_CH;  // staging chunks per thread = ds_writes = global loads per k-step
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int l32 = lane & 31, lh = lane >> 5;
-  const int ld_r = tid >> 3, ld_c = tid & 7;  // staging: row ld_r (+32 per extra chunk), 16-byte chunk ld_c
-  const bf16_t *u_base = p.u + ld_c * 8;
-  const bf16_t *w_base = p.W + ld_c * 8;
-  // LDS byte offset of this thread's staging chunk (row ld_r + 32 i keeps (row & 7) == (ld_r & 7))
-  const int st_off = ld_r * ROW_BYTES + ((ld_c ^ (ld_r & 7)) << 4);
-  // fragment read offsets: row (tile*32 + l32), chunk (2 kk + lh) swizzled by (row & 7) == (l32 & 7)
-  const int frag_u = (wm * (BM / 2) + l32) * ROW_BYTES;
-  const int frag_w = BM * ROW_BYTES + (wn * (BN / 2) + l32) * ROW_BYTES;
-  int coff[BK / 16];
-#pragma unroll
-  for (int kk = 0; kk < BK / 16; ++kk) coff[kk] = ((kk * 2 + lh) ^ (l32 & 7)) << 4;
-  const int nk = (p.k + BK - 1) / BK;
-  const int n_steady = (p.k / BK) - 2;  // k-steps kt with kt+2 a full step
-
-  auto tile_of = [&](int r) -> int {   // position in the tile sequence, or total_tiles when there is none
-    const int t = tile_sequence_index(p, r);
-    return t < 0 ? p.total_tiles : t;
-  };
-
-  int u_off[U_CH];   // element offsets; the host checks that they fit 31 bits
-  int w_off[W_CH];
-  uint4 u_reg[U_CH], w_reg[W_CH];
-  // bias of this lane's out-features; the accumulators START from it (so no epilogue load)
-  bf16x4 bias_r[TN][4];
-#pragma unroll
-  for (int a = 0; a < TN; ++a)
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) bias_r[a][g][e] = (bf16_t)0.f;
-
-#define GEMM_SET_TILE(TILE)                                                                        \
-  do {                                                                                             \
-    int tile_m_, tile_n_;                                                                          \
-    decode_tile(p, (TILE), tile_m_, tile_n_);                                                      \
-    row0 = (int64_t)tile_m_ * BM;                                                                  \
-    col0 = tile_n_ * BN;                                                                           \
-    _Pragma("unroll") for (int i = 0; i < U_CH; ++i) {                                             \
-      int64_t r_ = row0 + ld_r + 32 * i;                                                           \
-      if (r_ > p.N - 1) r_ = p.N - 1; /* overhanging rows re-read the last row; never stored */    \
-      u_off[i] = (int)(r_ * p.ld_u);                                                               \
-    }                                                                                              \
-    _Pragma("unroll") for (int i = 0; i < W_CH; ++i) {                                             \
-      int r_ = col0 + ld_r + 32 * i;                                                               \
-      if (r_ > p.n - 1) r_ = p.n - 1;                                                              \
-      w_off[i] = r_ * p.k;                                                                         \
-    }                                                                                              \
-  } while (0)
-
-  // Gate vectors of the tile's out-features for the (at most two) samples its rows belong to, kept
-  // in LDS past the stages: slot 0 = sample of the tile's first row, slot 1 = the next sample.
-  float4 gate_reg = make_float4(1.f, 1.f, 1.f, 1.f);
-  float *smem_gate = reinterpret_cast<float *>(smem + C::SMEM);
-  int64_t tile_sample0 = 0;      // sample of the first row of the tile whose gate is in gate_reg
-#define GEMM_GATE_LOAD()                                                                           \
-  do {                                                                                             \
-    if (EPI == 2 && p.gate_tab) {                                                                  \
-      tile_sample0 = row0 / p.tokens_per_sample;                                                   \
-      if (tid < 2 * (BN / 4)) {                                                                    \
-        const int which_ = tid / (BN / 4), c_ = tid - which_ * (BN / 4);                           \
-        int f_ = col0 + 4 * c_;                                                                    \
-        if (f_ > p.n - 4) f_ = p.n - 4;                                                            \
-        gate_reg = *reinterpret_cast<const float4 *>(p.gate_tab + f_);                             \
-        if (p.gate_c6) {                                                                           \
-          int64_t smp_ = tile_sample0 + which_;                                                    \
-          const int64_t last_ = (p.N - 1) / p.tokens_per_sample;                                   \
-          if (smp_ > last_) smp_ = last_;                                                          \
-          const float4 gc_ = *reinterpret_cast<const float4 *>(p.gate_c6 + smp_ * p.gate_c6_stride + f_); \
-          gate_reg.x += gc_.x; gate_reg.y += gc_.y; gate_reg.z += gc_.z; gate_reg.w += gc_.w;      \
-        }                                                                                          \
-      }                                                                                            \
-    }                                                                                              \
-  } while (0)
-
-#define GEMM_BIAS_LOAD()                                                                           \
-  do {                                                                                             \
-    if (p.bias) {                                                                                  \
-      _Pragma("unroll") for (int a = 0; a < TN; ++a)                                               \
-          _Pragma("unroll") for (int g = 0; g < 4; ++g) {                                          \
-        int f_ = col0 + wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;                                   \
-        if (f_ > p.n - 4) f_ = p.n - 4; /* overhanging features: a valid address, never stored */  \
-        bias_r[a][g] = *reinterpret_cast<const bf16x4 *>(p.bias + f_);                             \
-      }                                                                                            \
-    }                                                                                              \
-  } while (0)
-
-#define GEMM_G_LOAD(K0)                                                                            \
-  do {                                                                                             \
-    const int k0_ = (K0);                                                                          \
-    if (k0_ + ld_c * 8 < p.k) {                                                                    \
-      _Pragma("unroll") for (int i = 0; i < U_CH; ++i)                                             \
-          u_reg[i] = *reinterpret_cast<const uint4 *>(u_base + u_off[i] + k0_);                    \
-      _Pragma("unroll") for (int i = 0; i < W_CH; ++i)                                             \
-          w_reg[i] = *reinterpret_cast<const uint4 *>(w_base + w_off[i] + k0_);                    \
-    } else { /* k tail: zero-fill both operands */                                                 \
-      _Pragma("unroll") for (int i = 0; i < U_CH; ++i) u_reg[i] = make_uint4(0u, 0u, 0u, 0u);      \
-      _Pragma("unroll") for (int i = 0; i < W_CH; ++i) w_reg[i] = make_uint4(0u, 0u, 0u, 0u);      \
-    }                                                                                              \
-  } while (0)
-
-#define GEMM_G_LOAD_FULL(K0)                                                                       \
-  do {                                                                                             \
-    const int k0_ = (K0);                                                                          \
-    _Pragma("unroll") for (int i = 0; i < U_CH; ++i)                                               \
-        u_reg[i] = *reinterpret_cast<const uint4 *>(u_base + u_off[i] + k0_);                      \
-    _Pragma("unroll") for (int i = 0; i < W_CH; ++i)                                               \
-        w_reg[i] = *reinterpret_cast<const uint4 *>(w_base + w_off[i] + k0_);                      \
-  } while (0)
-
-#define GEMM_S_STORE(STAGE_IDX)                                                                    \
-  do {                                                                                             \
-    unsigned char *su_ = smem + (STAGE_IDX) * STAGE + st_off;                                      \
-    unsigned char *sw_ = su_ + BM * ROW_BYTES;                                                     \
-    _Pragma("unroll") for (int i = 0; i < U_CH; ++i)                                               \
-        *reinterpret_cast<uint4 *>(su_ + i * 32 * ROW_BYTES) = u_reg[i];                           \
-    _Pragma("unroll") for (int i = 0; i < W_CH; ++i)                                               \
-        *reinterpret_cast<uint4 *>(sw_ + i * 32 * ROW_BYTES) = w_reg[i];                           \
-  } while (0)
-
-#define GEMM_READ_FRAGS(BUF, STAGE_IDX, KK)                                                        \
-  do {                                                                                             \
-    const unsigned char *sb_ = smem + (STAGE_IDX) * STAGE + coff[KK];                              \
-    _Pragma("unroll") for (int b = 0; b < TM; ++b)                                                 \
-        uf[BUF][b] = *reinterpret_cast<const bf16x8 *>(sb_ + frag_u + b * 32 * ROW_BYTES);         \
-    _Pragma("unroll") for (int a = 0; a < TN; ++a)                                                 \
-        wf[BUF][a] = *reinterpret_cast<const bf16x8 *>(sb_ + frag_w + a * 32 * ROW_BYTES);         \
-  } while (0)
-
-#define GEMM_MFMAS(BUF)                                                                            \
-  do {                                                                                             \
-    _Pragma("unroll") for (int a = 0; a < TN; ++a)                                                 \
-        _Pragma("unroll") for (int b = 0; b < TM; ++b)                                             \
-            acc[a][b] = mfma32(wf[BUF][a], uf[BUF][b], acc[a][b]);                                 \
-  } while (0)
-
-  int64_t row0 = 0;
-  int col0 = 0;
-  int tile = tile_of(0);
-  if (tile >= p.total_tiles) return;
-  GEMM_SET_TILE(tile);
-  GEMM_BIAS_LOAD();
-  GEMM_GATE_LOAD();
-  GEMM_G_LOAD(0);
-
-  for (int round = 0;; ++round) {
-    // ---- prologue: the registers hold k-step 0 of this tile
-    const int64_t my_row0 = row0;
-    const int my_col0 = col0;
-    const int64_t my_sample0 = tile_sample0;
-    GEMM_S_STORE(0);
-    if (EPI == 2 && tid < 2 * (BN / 4)) *reinterpret_cast<float4 *>(smem_gate + tid * 4) = gate_reg;
-    if (nk > 1) GEMM_G_LOAD(BK);
-    floatx16 acc[TN][TM];
-#pragma unroll
-    for (int a = 0; a < TN; ++a)
-#pragma unroll
-      for (int b = 0; b < TM; ++b)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[a][b][e] = (float)bias_r[a][e >> 2][e & 3];
-    lds_barrier();
-
-    bf16x8 uf[2][TM], wf[2][TN];
-    GEMM_READ_FRAGS(0, 0, 0);
-    int kt = 0;
-    // ---- steady state: k-steps kt+1 and kt+2 exist and kt+2 is a full step; no branches inside,
-    // so each sub-step is one scheduling region with an explicit issue order
-    for (; kt < n_steady; ++kt) {
-      const int cur = kt & 1;
-      // sub-step 0: stage k-step kt+1 into the other buffer
-      GEMM_READ_FRAGS(1, cur, 1);
-      GEMM_S_STORE(cur ^ 1);
-      GEMM_MFMAS(0);
-      __builtin_amdgcn_sched_group_barrier(SG_DS_RD, NFRAG, 0);
-      sched_interleave<SG_DS_WR, 0, NMFMA, NST>();
-      __builtin_amdgcn_sched_barrier(0);
-      // sub-step 1: issue the global loads of k-step kt+2
-      GEMM_READ_FRAGS(0, cur, 2);
-      GEMM_G_LOAD_FULL((kt + 2) * BK);
-      GEMM_MFMAS(1);
-      __builtin_amdgcn_sched_group_barrier(SG_DS_RD, NFRAG, 0);
-      sched_interleave<SG_VMEM_RD, 0, NMFMA, NST>();
-      __builtin_amdgcn_sched_barrier(0);
-      // sub-step 2
-      GEMM_READ_FRAGS(1, cur, 3);
-      __builtin_amdgcn_sched_barrier(0);
-      GEMM_MFMAS(0);
-      __builtin_amdgcn_sched_barrier(0);
-      // Past this barrier every wave's last read of the current stage has returned and its
-      // writes of the next stage are done: the next stage may be read, and the following
-      // k-step may overwrite the current one.
-      lds_barrier();
-      // sub-step 3: first fragments of the next stage
-      GEMM_READ_FRAGS(0, cur ^ 1, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      GEMM_MFMAS(1);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // ---- the last k-steps (and the k tail, zero-filled)
-    for (; kt < nk; ++kt) {
-      const int cur = kt & 1;
-      const bool has_next = kt + 1 < nk;
-      if (has_next) GEMM_S_STORE(cur ^ 1);
-      GEMM_READ_FRAGS(1, cur, 1);
-      GEMM_MFMAS(0);
-      if (kt + 2 < nk) GEMM_G_LOAD((kt + 2) * BK);
-      GEMM_READ_FRAGS(0, cur, 2);
-      GEMM_MFMAS(1);
-      GEMM_READ_FRAGS(1, cur, 3);
-      GEMM_MFMAS(0);
-      lds_barrier();
-      if (has_next) GEMM_READ_FRAGS(0, cur ^ 1, 0);
-      GEMM_MFMAS(1);
-    }
-    // every wave is past the last barrier of the k loop: no LDS read of the stages is pending
-
-    // ---- epilogue.  acc[a][b][4g+e] = C[token tb + l32][feature fb + 8g + 4 lh + e]
-    // ---- next tile: start its first global loads now, they land during the epilogue
-    const int next_tile = (round + 1 < p.rounds) ? tile_of(round + 1) : p.total_tiles;
-    const bool more = next_tile < p.total_tiles;
-    if (more) {
-      GEMM_SET_TILE(next_tile);
-      GEMM_BIAS_LOAD();
-      GEMM_GATE_LOAD();
-      GEMM_G_LOAD(0);
-    }
-
-    gemm_epilogue<BM, BN, EPI>(acc, smem, smem_gate, p, my_row0, my_col0, my_sample0, tid, wm, wn, l32, lh);
-    if (!more) break;
-    if constexpr (EPI != 2) lds_barrier();   // staged rows are read by other waves until here
-    tile = next_tile;
-  }
-#undef GEMM_SET_TILE
-#undef GEMM_BIAS_LOAD
-#undef GEMM_GATE_LOAD
-#undef GEMM_G_LOAD
-#undef GEMM_G_LOAD_FULL
-#undef GEMM_S_STORE
-#undef GEMM_READ_FRAGS
-#undef GEMM_MFMAS
-}
-
-// ---------------------------------------------------------------------------------------------
-// Direct-to-LDS variant (k a multiple of 32).  Operand tiles go global -> LDS with 16-byte
-// global_load_lds: no staging registers, no ds_write, and the loads of k-step i+3 are in flight
-// while k-step i is multiplied (four LDS stages of (BM+BN) rows x 64 B).  A wave-wide load places
-// lane l's piece at LDS base + 16 l, i.e. 16 consecutive 64-byte rows; the XOR swizzle that keeps
-// the fragment reads conflict-free (chunk slot = chunk ^ ((row >> 1) & 3)) is therefore applied
-// to the GLOBAL address each lane fetches from.  Completion is tracked with the vector-memory
-// counter, which retires in order: before the barrier of k-step i each wave waits until at most
-// the loads of k-steps i+2 and i+3 are outstanding, so past the barrier stage i+1 is complete.
-// ---------------------------------------------------------------------------------------------
-constexpr int DL_BK = 32;
-constexpr int DL_ROW = 64;   // bytes per LDS row
-constexpr int DL_NS = 4;     // stages
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 typedef __attribute__((address_space(1))) const void *gbl_ptr_t;
 
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  else if constexpr (N == 7) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
-  else if constexpr (N == 14) asm volatile("s_waitcnt vmcnt(14)" ::: "memory");
-  else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  else static_assert(N == 0, "unsupported count");
-}
+template <int NJ_>
+struct LoadCount { static constexpr int value = NJ_; };
 
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void k_gemm_dl(GemmParams p) {
-  using C = GemmCfg<BM, BN>;
-  constexpr int TM = BM / 64, TN = BN / 64;
-  constexpr int STAGE = (BM + BN) * DL_ROW;
-  constexpr int NI = (BM + BN) / 16;   // wave-wide loads per k-step (16 rows each)
-  constexpr int NJ = NI / 4;           // per wave
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI>
+__global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
+  using C = GemmCfg<WGM, WGN, TM, TN, NS>;
+  constexpr int BM = C::BM, BN = C::BN, STAGE = C::STAGE, NW = C::NW;
   constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
-  static_assert(NI % 4 == 0, "loads must divide over the four waves");
-  static_assert(DL_NS * STAGE <= C::SMEM, "stages must fit the shared allocation");
-  static_assert(NJ == 7 || NJ == 4, "wait_vmcnt covers these counts");
+  constexpr int AHEAD = NS - 1;          // k-steps in flight ahead of the one being multiplied
+  // The bf16 epilogues stage in the last two LDS stages only, so the next tile's first k-steps are
+  // fetched while the current tile is written out; the fp32 epilogue needs the whole LDS.
+  constexpr bool EARLY_FETCH = EPI != 2;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   float *smem_gate = reinterpret_cast<float *>(smem + C::SMEM);
+  unsigned char *smem_bias = smem + C::SMEM + C::GATE_BYTES;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave - wm * WGN;
   const int l32 = lane & 31, lh = lane >> 5;
-  const int nk = p.k / DL_BK;
+  const int nk = (p.k + BK - 1) / BK;
+  const int nk_full = p.k / BK;
 
-  // fragment reads: row (tile*32 + l32) of 64 B, chunk (2 kk + lh) at slot chunk ^ ((row >> 1) & 3)
-  const int frag_u = (wm * (BM / 2) + l32) * DL_ROW;
-  const int frag_w = BM * DL_ROW + (wn * (BN / 2) + l32) * DL_ROW;
+  // fragment reads: row (tile*32 + l32) of 64 B, chunk (2 kk + lh) at slot chunk ^ ((row >> 2) & 3)
+  const int frag_u = (wm * (TM * 32) + l32) * ROW;
+  const int frag_w = BM * ROW + (wn * (TN * 32) + l32) * ROW;
   int coff[2];
 #pragma unroll
-  for (int kk = 0; kk < 2; ++kk) coff[kk] = ((kk * 2 + lh) ^ ((l32 >> 1) & 3)) << 4;
-  // loads: instruction g = wave*NJ + j covers tile rows 16 g .. 16 g + 15; this lane: row lane/4, slot lane%4
+  for (int kk = 0; kk < 2; ++kk) coff[kk] = ((kk * 2 + lh) ^ ((l32 >> 2) & 3)) << 4;
+  // loads: this wave's j-th instruction is number g = wave + NW j of the k-step and covers tile rows
+  // 16 g .. 16 g + 15 (token rows first, then W rows); this lane: row lane/4, slot lane%4
   const int ld_row = lane >> 2;
-  const int ld_chunk = ((lane & 3) ^ ((ld_row >> 1) & 3)) * 8;   // element offset of the global chunk to fetch
+  const int ld_chunk = ((lane & 3) ^ ((ld_row >> 2) & 3)) * 8;   // element offset of the global chunk to fetch
+  const unsigned bias_lds = lds_offset(smem_bias) + (wn * (TN * 32) + 4 * lh) * 2;
 
-  int src_off[NJ];   // element offset of this lane's piece at k = 0 (u or W, by instruction)
+  // The whole tile loop, compiled per NJ = this wavefront's loads per k-step.
+  auto run = [&](auto nj_tag) {
+    constexpr int NJ = decltype(nj_tag)::value;
+    constexpr int PENDING = (NS - 2) * NJ;   // loads that may still be outstanding when k-step i+1 is needed
+    int src_off[NJ];                         // element offset of this lane's piece at k = 0 (u or W, by instruction)
 
-#define DL_ISSUE(KT)                                                                               \
+#define DL_ISSUE(KT, ST)                                                                           \
   do {                                                                                             \
-    const int k0_ = (KT) * DL_BK;                                                                  \
-    unsigned char *sb_ = smem + ((KT) & (DL_NS - 1)) * STAGE + wave * NJ * 1024;                   \
+    const int k0_ = (KT) * BK;                                                                     \
+    unsigned char *sb_ = smem + (ST) * STAGE + wave * 1024;                                        \
     _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                               \
-      const bf16_t *src_ = ((wave * NJ + j) * 16 < BM ? p.u : p.W) + src_off[j] + k0_;             \
-      __builtin_amdgcn_global_load_lds((gbl_ptr_t)src_, (lds_ptr_t)(sb_ + j * 1024), 16, 0, 0);    \
+      const bf16_t *src_ = ((wave + NW * j) * 16 < BM ? p.u : p.W) + src_off[j] + k0_;             \
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)src_, (lds_ptr_t)(sb_ + j * (NW * 1024)), 16, 0, 0); \
     }                                                                                              \
   } while (0)
 
-#define DL_READ_FRAGS(BUF, KT, KK)                                                                 \
+    // the last, partial k-step: lanes whose chunk starts at or past k fetch zeros instead
+#define DL_ISSUE_TAIL(KT, ST)                                                                      \
   do {                                                                                             \
-    const unsigned char *sb_ = smem + ((KT) & (DL_NS - 1)) * STAGE + coff[KK];                     \
+    const int k0_ = (KT) * BK;                                                                     \
+    const bool in_ = k0_ + ld_chunk < p.k;                                                         \
+    unsigned char *sb_ = smem + (ST) * STAGE + wave * 1024;                                        \
+    _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                               \
+      const bf16_t *src_ = ((wave + NW * j) * 16 < BM ? p.u : p.W) + src_off[j] + k0_;             \
+      if (!in_) src_ = reinterpret_cast<const bf16_t *>(k_zero_block);                             \
+      __builtin_amdgcn_global_load_lds((gbl_ptr_t)src_, (lds_ptr_t)(sb_ + j * (NW * 1024)), 16, 0, 0); \
+    }                                                                                              \
+  } while (0)
+
+#define DL_READ_FRAGS(BUF, ST, KK)                                                                 \
+  do {                                                                                             \
+    const unsigned char *sb_ = smem + (ST) * STAGE + coff[KK];                                     \
     _Pragma("unroll") for (int b = 0; b < TM; ++b)                                                 \
-        uf[BUF][b] = *reinterpret_cast<const bf16x8 *>(sb_ + frag_u + b * 32 * DL_ROW);            \
+        uf[BUF][b] = *reinterpret_cast<const bf16x8 *>(sb_ + frag_u + b * 32 * ROW);               \
     _Pragma("unroll") for (int a = 0; a < TN; ++a)                                                 \
-        wf[BUF][a] = *reinterpret_cast<const bf16x8 *>(sb_ + frag_w + a * 32 * DL_ROW);            \
+        wf[BUF][a] = *reinterpret_cast<const bf16x8 *>(sb_ + frag_w + a * 32 * ROW);               \
   } while (0)
 
 #define DL_MFMAS(BUF)                                                                              \
@@ -592,110 +430,168 @@ __global__ __launch_bounds__(256) void k_gemm_dl(GemmParams p) {
             acc[a][b] = mfma32(wf[BUF][a], uf[BUF][b], acc[a][b]);                                 \
   } while (0)
 
-  for (int round = 0; round < p.rounds; ++round) {
-    const int tile = tile_sequence_index(p, round);
-    if (tile < 0) break;
+#define NEXT_STAGE(S) ((S) + 1 == NS ? 0 : (S) + 1)
+
+    // Start of a tile's operand stream: source offsets, the tile's bias (one wavefront fetches it,
+    // ahead of everything else, so it has landed when k-step 0 has), k-steps 0 .. AHEAD-1.
+    auto begin_tile = [&](int64_t row0, int col0, int first_steps) {
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int R = (wave + NW * j) * 16 + ld_row;
+        if (R < BM) {
+          int64_t t = row0 + R;
+          if (t > p.N - 1) t = p.N - 1;           // overhanging rows re-read the last row; never stored
+          src_off[j] = (int)(t * p.ld_u) + ld_chunk;
+        } else {
+          int f = col0 + R - BM;
+          if (f > p.n - 1) f = p.n - 1;
+          src_off[j] = f * p.k + ld_chunk;
+        }
+      }
+      if (p.bias && wave == 0 && lane < BN / 8) {
+        int f = col0 + lane * 8;
+        if (f > p.n - 8) f = p.n - 8;             // overhanging features: a valid address, never stored
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p.bias + f), (lds_ptr_t)smem_bias, 16, 0, 0);
+      }
+#pragma unroll
+      for (int s = 0; s < AHEAD; ++s) {
+        if (s >= first_steps) break;
+        if (s < nk_full) DL_ISSUE(s, s);
+        else if (s < nk) DL_ISSUE_TAIL(s, s);
+      }
+    };
+    // the remaining k-steps of the first AHEAD, once the epilogue has left the last stages
+    auto finish_begin = [&](int first_steps) {
+#pragma unroll
+      for (int s = 0; s < AHEAD; ++s) {
+        if (s < first_steps) continue;
+        if (s < nk_full) DL_ISSUE(s, s);
+        else if (s < nk) DL_ISSUE_TAIL(s, s);
+      }
+    };
+
+    int tile = tile_sequence_index(p, 0);
+    if (tile < 0) return;
     int tile_m, tile_n;
     decode_tile(p, tile, tile_m, tile_n);
-    const int64_t row0 = (int64_t)tile_m * BM;
-    const int col0 = tile_n * BN;
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      const int R = (wave * NJ + j) * 16 + ld_row;
-      if (R < BM) {
-        int64_t t = row0 + R;
-        if (t > p.N - 1) t = p.N - 1;           // overhanging rows re-read the last row; never stored
-        src_off[j] = (int)(t * p.ld_u) + ld_chunk;
-      } else {
-        int f = col0 + R - BM;
-        if (f > p.n - 1) f = p.n - 1;
-        src_off[j] = f * p.k + ld_chunk;
-      }
-    }
-    // bias and gate first: the memory counter retires in order, so what is needed first is issued first
-    bf16x4 bias_r[TN][4];
-#pragma unroll
-    for (int a = 0; a < TN; ++a)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) bias_r[a][g][e] = (bf16_t)0.f;
-        if (p.bias) {
-          int f = col0 + wn * (BN / 2) + a * 32 + 8 * g + 4 * lh;
+    int64_t row0 = (int64_t)tile_m * BM;
+    int col0 = tile_n * BN;
+    begin_tile(row0, col0, AHEAD);
+
+    for (int round = 0;; ++round) {
+      int64_t sample0 = 0;
+      if (EPI == 2 && p.gate_tab) {
+        sample0 = row0 / p.tokens_per_sample;
+        if (tid < 2 * (BN / 4)) {
+          const int which = tid / (BN / 4), c = tid - which * (BN / 4);
+          int f = col0 + 4 * c;
           if (f > p.n - 4) f = p.n - 4;
-          bias_r[a][g] = *reinterpret_cast<const bf16x4 *>(p.bias + f);
+          float4 gt = *reinterpret_cast<const float4 *>(p.gate_tab + f);
+          if (p.gate_c6) {
+            int64_t smp = sample0 + which;
+            const int64_t last = (p.N - 1) / p.tokens_per_sample;
+            if (smp > last) smp = last;
+            const float4 gc = *reinterpret_cast<const float4 *>(p.gate_c6 + smp * p.gate_c6_stride + f);
+            gt.x += gc.x; gt.y += gc.y; gt.z += gc.z; gt.w += gc.w;
+          }
+          *reinterpret_cast<float4 *>(smem_gate + tid * 4) = gt;
         }
       }
-    int64_t sample0 = 0;
-    if (EPI == 2 && p.gate_tab) {
-      sample0 = row0 / p.tokens_per_sample;
-      if (tid < 2 * (BN / 4)) {
-        const int which = tid / (BN / 4), c = tid - which * (BN / 4);
-        int f = col0 + 4 * c;
-        if (f > p.n - 4) f = p.n - 4;
-        float4 gt = *reinterpret_cast<const float4 *>(p.gate_tab + f);
-        if (p.gate_c6) {
-          int64_t smp = sample0 + which;
-          const int64_t last = (p.N - 1) / p.tokens_per_sample;
-          if (smp > last) smp = last;
-          const float4 gc = *reinterpret_cast<const float4 *>(p.gate_c6 + smp * p.gate_c6_stride + f);
-          gt.x += gc.x; gt.y += gc.y; gt.z += gc.z; gt.w += gc.w;
-        }
-        *reinterpret_cast<float4 *>(smem_gate + tid * 4) = gt;
-      }
-    }
-    DL_ISSUE(0);
-    if (nk > 1) DL_ISSUE(1);
-    if (nk > 2) DL_ISSUE(2);
-
-    floatx16 acc[TN][TM];
-#pragma unroll
-    for (int a = 0; a < TN; ++a)
-#pragma unroll
-      for (int b = 0; b < TM; ++b)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[a][b][e] = (float)bias_r[a][e >> 2][e & 3];
-
-    if (nk > 2) wait_vmcnt<2 * NJ>();
-    else if (nk > 1) wait_vmcnt<NJ>();
-    else wait_vmcnt<0>();
-    lds_barrier();
-
-    bf16x8 uf[2][TM], wf[2][TN];
-    DL_READ_FRAGS(0, 0, 0);
-    int kt = 0;
-    // ---- steady state: k-steps kt+1 .. kt+3 exist; no branches, issue order pinned
-    for (; kt + 3 < nk; ++kt) {
-      DL_READ_FRAGS(1, kt, 1);
-      DL_ISSUE(kt + 3);
-      DL_MFMAS(0);
-      __builtin_amdgcn_sched_group_barrier(SG_DS_RD, NFRAG, 0);
-      sched_interleave<SG_VMEM_RD, 0, NMFMA, NJ>();
-      __builtin_amdgcn_sched_barrier(0);
-      wait_vmcnt<2 * NJ>();   // k-step kt+1 has landed (this wave's part)
-      lds_barrier();          // ... everyone's part; and every wave is done reading stage kt
-      DL_READ_FRAGS(0, kt + 1, 0);
-      __builtin_amdgcn_sched_barrier(0);
-      DL_MFMAS(1);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // ---- last k-steps
-    for (; kt < nk; ++kt) {
-      DL_READ_FRAGS(1, kt, 1);
-      DL_MFMAS(0);
-      if (kt + 2 < nk) wait_vmcnt<NJ>();
+      // k-step 0 (and the bias) must have landed; up to AHEAD-1 later steps may be pending
+      if (nk >= AHEAD) wait_vmcnt<PENDING>();
       else wait_vmcnt<0>();
       lds_barrier();
-      if (kt + 1 < nk) DL_READ_FRAGS(0, kt + 1, 0);
-      DL_MFMAS(1);
+
+      // the accumulators start from the bias
+      floatx16 acc[TN][TM];
+#pragma unroll
+      for (int a = 0; a < TN; ++a) {
+        uint2 bq[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) bq[g] = make_uint2(0u, 0u);
+        if (p.bias) lds_read4_b64(bq, bias_lds + a * 64);
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            acc[a][b][4 * g + 0] = __uint_as_float(bq[g].x << 16);
+            acc[a][b][4 * g + 1] = __uint_as_float(bq[g].x & 0xffff0000u);
+            acc[a][b][4 * g + 2] = __uint_as_float(bq[g].y << 16);
+            acc[a][b][4 * g + 3] = __uint_as_float(bq[g].y & 0xffff0000u);
+          }
+      }
+
+      bf16x8 uf[2][TM], wf[2][TN];
+      DL_READ_FRAGS(0, 0, 0);
+      int kt = 0;
+      int st = 0;                 // stage of k-step kt
+      int st_new = AHEAD;         // stage that k-step kt + AHEAD goes to (== stage of kt-1)
+      // ---- steady state: k-step kt + AHEAD exists and is a full step; no branches, issue order pinned.
+      // Each half issues one MFMA first, then the LDS reads of the NEXT half's fragments, then the
+      // rest: the wait that the compiler places before the first MFMA (it always waits for every
+      // LDS read issued so far) then covers only reads issued a whole half earlier.
+      for (; kt + AHEAD < nk_full; ++kt) {
+        const int st_next = NEXT_STAGE(st);
+        DL_READ_FRAGS(1, st, 1);
+        DL_ISSUE(kt + AHEAD, st_new);
+        DL_MFMAS(0);
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(SG_DS_RD, NFRAG, 0);
+        sched_interleave<SG_VMEM_RD, 0, NMFMA - 1, NJ>();
+        __builtin_amdgcn_sched_barrier(0);
+        wait_vmcnt<PENDING>();        // k-step kt+1 has landed (this wave's part); kt+2 .. kt+AHEAD may be pending
+        lds_barrier();                // ... everyone's part; and every wave is done reading stage kt
+        DL_READ_FRAGS(0, st_next, 0);
+        DL_MFMAS(1);
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(SG_DS_RD, NFRAG, 0);
+        __builtin_amdgcn_sched_group_barrier(SG_MFMA, NMFMA - 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        st_new = st;
+        st = st_next;
+      }
+      // ---- last k-steps: at most one more load (the partial step), then drain
+      for (; kt < nk; ++kt) {
+        const int st_next = NEXT_STAGE(st);
+        DL_READ_FRAGS(1, st, 1);
+        if (kt + AHEAD < nk) DL_ISSUE_TAIL(kt + AHEAD, st_new);
+        DL_MFMAS(0);
+        wait_vmcnt<0>();
+        lds_barrier();
+        if (kt + 1 < nk) DL_READ_FRAGS(0, st_next, 0);
+        DL_MFMAS(1);
+        st_new = st;
+        st = st_next;
+      }
+      // every wave is past the last barrier of the k loop: no LDS read of the stages is pending
+
+      const int64_t my_row0 = row0;
+      const int my_col0 = col0;
+      const int next = round + 1 < p.rounds ? tile_sequence_index(p, round + 1) : -1;
+      if (next >= 0) {
+        decode_tile(p, next, tile_m, tile_n);
+        row0 = (int64_t)tile_m * BM;
+        col0 = tile_n * BN;
+        if (EARLY_FETCH) begin_tile(row0, col0, C::EARLY_STEPS);
+      }
+      gemm_epilogue<C, TM, TN, EPI>(acc, smem, smem_gate, p, my_row0, my_col0, sample0, tid, wm, wn, l32, lh);
+      if (next < 0) break;
+      if (EARLY_FETCH) finish_begin(C::EARLY_STEPS);
+      else begin_tile(row0, col0, AHEAD);
     }
-    // every wave is past the last barrier of the k loop: no LDS read of the stages is pending
-    gemm_epilogue<BM, BN, EPI>(acc, smem, smem_gate, p, row0, col0, sample0, tid, wm, wn, l32, lh);
-    if constexpr (EPI != 2) lds_barrier();   // staged rows are read by other waves until here
-  }
 #undef DL_ISSUE
+#undef DL_ISSUE_TAIL
 #undef DL_READ_FRAGS
 #undef DL_MFMAS
+#undef NEXT_STAGE
+  };
+
+  if constexpr (C::N_HI == 0) {
+    run(LoadCount<C::NJ_LO>{});
+  } else {
+    if (wave < C::N_HI) run(LoadCount<C::NJ_HI>{});
+    else run(LoadCount<C::NJ_LO>{});
+  }
 }
 
 int num_cus() {
@@ -710,13 +606,16 @@ int num_cus() {
   return cus;
 }
 
-template <int BM, int BN, int EPI, bool DIRECT>
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI>
 int launch_one(const GemmParams &p0, hipStream_t s) {
-  using C = GemmCfg<BM, BN>;
+  using C = GemmCfg<WGM, WGN, TM, TN, NS>;
+  constexpr int LDS_BYTES = C::SMEM + C::EXTRA_BYTES;
+  static_assert(LDS_BYTES <= 160 * 1024, "the tile's stages must fit the LDS");
+  constexpr int WG_PER_CU = (160 * 1024) / LDS_BYTES >= 2 && C::NW <= 4 ? 2 : 1;
   GemmParams p = p0;
-  const int64_t tiles_m = (p.N + BM - 1) / BM;
+  const int64_t tiles_m = (p.N + C::BM - 1) / C::BM;
   p.tiles_m = (int)tiles_m;
-  p.tiles_n = (p.n + BN - 1) / BN;
+  p.tiles_n = (p.n + C::BN - 1) / C::BN;
   // width of an out-feature group: at most 8 tiles, as even as the tile count allows
   const int n_groups = (p.tiles_n + 7) / 8;
   p.group_w = (p.tiles_n + n_groups - 1) / n_groups;
@@ -726,36 +625,30 @@ int launch_one(const GemmParams &p0, hipStream_t s) {
     return -2;
   }
   p.total_tiles = (int)total;
-  // one workgroup per CU (the LDS stages leave room for one); a multiple of 8 so that every
-  // round gives each XCD a contiguous run of tiles
-  int grid = num_cus() & ~7;
+  // as many workgroups as the chip holds at once; a multiple of 8 so that every round gives
+  // each XCD a contiguous run of tiles
+  int grid = (num_cus() * WG_PER_CU) & ~7;
   if (grid < 8) grid = 8;
   if (total <= grid) grid = (int)((total + 7) & ~(int64_t)7);
   p.rounds = (int)(((total + 7) / 8 + grid / 8 - 1) / (grid / 8));
   static bool attr_set = false;  // benign race: the attribute is idempotent
   if (!attr_set) {
-    const void *fn = DIRECT ? reinterpret_cast<const void *>(&k_gemm_dl<BM, BN, EPI>)
-                            : reinterpret_cast<const void *>(&k_gemm_bf16<BM, BN, EPI>);
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, C::SMEM + 2 * BN * 4);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<WGM, WGN, TM, TN, NS, EPI>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e != hipSuccess) return ddit::hip_fail(e, "gemm hipFuncSetAttribute");
     attr_set = true;
   }
-  if (DIRECT)
-    hipLaunchKernelGGL((k_gemm_dl<BM, BN, EPI>), dim3((unsigned)grid), dim3(256), C::SMEM + 2 * BN * 4, s, p);
-  else
-    hipLaunchKernelGGL((k_gemm_bf16<BM, BN, EPI>), dim3((unsigned)grid), dim3(256), C::SMEM + 2 * BN * 4, s, p);
+  hipLaunchKernelGGL((k_gemm_bf16<WGM, WGN, TM, TN, NS, EPI>), dim3((unsigned)grid), dim3(C::NT), LDS_BYTES, s, p);
   return ddit::hip_fail(hipGetLastError(), "gemm launch");
 }
 
 template <int EPI>
 int launch_epi(const GemmParams &p, hipStream_t s) {
-  // 192-wide feature tiles divide 1152, 3456, 4608 and 2304 exactly; narrow outputs and
-  // short token counts take the smaller tile so more than a handful of CUs get work.
-  const int64_t big_tiles = ((p.N + 255) / 256) * ((p.n + 191) / 192);
-  const bool big = big_tiles >= 128 && (p.n % 192 == 0 || p.n > 1024);
-  // the direct-to-LDS kernel cannot zero-fill a k tail
-  if (p.k % DL_BK == 0) return big ? launch_one<256, 192, EPI, true>(p, s) : launch_one<128, 128, EPI, true>(p, s);
-  return big ? launch_one<256, 192, EPI, false>(p, s) : launch_one<128, 128, EPI, false>(p, s);
+  // 384-wide feature tiles divide 1152, 3456 and 4608 exactly; narrow outputs and short token
+  // counts take the small tile so that more than a handful of CUs get work.
+  const int64_t big_tiles = ((p.N + 191) / 192) * ((p.n + 383) / 384);
+  const bool big = big_tiles >= 128 && p.n >= 384 && (p.n % 384 == 0 || p.n > 2048);
+  return big ? launch_one<2, 4, 3, 3, 4, EPI>(p, s) : launch_one<2, 2, 2, 2, 4, EPI>(p, s);
 }
 
 }  // namespace
