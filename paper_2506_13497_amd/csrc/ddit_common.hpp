@@ -66,6 +66,7 @@ struct AttnArgs {
   int H, dh;
 };
 int launch_flash_attn(const AttnArgs &a, hipStream_t s);
+int temporal_attn_max_T();   // longest sequence the dedicated temporal kernel takes
 int launch_temporal_attn(const void *q, const void *k, const void *v, void *o, float *lse, int64_t ld_q,
                          int64_t ld_kv, int64_t ld_o, int B, int T, int S, int H, int dh, hipStream_t s);
 

@@ -125,6 +125,11 @@ int run_attention(ddit_attn_kind kind, const Dims &d, const void *q, const void 
       a.Lq = a.Lk_max = (int)d.S;
       break;
     case DDIT_ATTN_TEMPORAL:
+      // short sequences (one matrix-core tile of frames): the dedicated kernel; longer ones take
+      // the generic streaming kernel with strided groups
+      if (d.T <= temporal_attn_max_T())
+        return launch_temporal_attn(q, k, v, o, lse, ld_q, ld_kv, ld_o, (int)d.B, (int)d.T, (int)d.S, (int)d.H,
+                                    (int)d.dh, s);
       a.n_groups = (int)(d.B * d.S); a.g_inner = (int)d.S;
       a.q_outer = a.kv_outer = d.T * d.S; a.q_inner = a.kv_inner = 1;
       a.q_tok_step = a.kv_tok_step = d.S;
