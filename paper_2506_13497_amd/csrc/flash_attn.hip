@@ -18,18 +18,25 @@
 // kernel).  In the result layout a lane owns ONE query (column l%32) and 16 of every 32
 // keys, so the row maximum is a register reduction plus one exchange with lane l^32.
 // The probabilities P^T, rounded to bf16, are then already laid out as the second
-// operand of O^T = V^T P^T, provided V^T's key axis is enumerated in the same order:
-// V is transposed on its way into LDS (two keys packed per 32-bit write) with the keys
-// of each group of 16 stored in the order the accumulator registers enumerate them.
-// The head dim 72 is padded to 80 for Q K^T (zeros in registers, never in memory) and to
-// 96 rows for V^T; one of the spare V^T rows is set to 1 so that the same MFMAs that form
-// O also accumulate the softmax denominator (of the bf16-rounded probabilities used).
+// operand of O^T = V^T P^T, provided the first operand V^T enumerates the keys in the
+// order of the accumulator registers.  V stays row-major [key][d] in LDS, exactly as it
+// comes from memory; the transposition happens in the LDS read: ds_read_b64_tr_b16 hands
+// each lane of a 16-lane block four KEYS' values of its own d (lane i of the block
+// supplies the address of the 8-byte piece "key i/4, d-group i%4"; it receives element i%4
+// of the pieces of lanes i/4, 4+i/4, 8+i/4, 12+i/4), two such reads per operand.
+// The head dim 72 is padded to 80 for Q K^T (zero Q in registers) and to 96 rows for V^T
+// (rows past the head dim read neighbouring data and produce rows of O^T that are never
+// stored); the lanes of row 72 substitute ones, so that the same MFMAs that form O also
+// accumulate the softmax denominator (of the bf16-rounded probabilities used).
 //
-// Data movement.  K tiles go global -> LDS directly (16 bytes per lane, no registers),
-// packed at a 144-byte row pitch for dh 72 (16-byte reads of 8 consecutive rows then
-// cover all 32 banks once) or at 128 bytes with an XOR chunk swizzle for dh 64.  V goes
-// through registers for the transposition.  Two stages; the next tile's loads are in
-// flight during the current tile's MFMAs; one barrier per tile.
+// Data movement.  K and V tiles go global -> LDS directly (16 bytes per lane, no
+// registers), packed at a 144-byte row pitch for dh 72 or at 128 bytes with an XOR chunk
+// swizzle for dh 64.  Two stages; the next tile's loads are in flight during the current
+// tile's arithmetic; one barrier per tile.
+//
+// Instruction order.  The inner loop is bound by the vector ALU (one exponential per
+// score is a quarter-rate instruction), so the MFMAs are threaded through it by hand: see
+// tile_step.
 #include "ddit_common.hpp"
 
 namespace {
@@ -39,6 +46,8 @@ constexpr int KT = 64;    // keys per LDS tile
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 typedef __attribute__((address_space(1))) const void *gbl_ptr_t;
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) shortx4 *lds_s4_ptr_t;
 
 struct FlashParams {
   const bf16_t *q, *k, *v;
@@ -49,6 +58,8 @@ struct FlashParams {
   int64_t q_outer, q_inner, kv_outer, kv_inner;
   int64_t q_tok_step, kv_tok_step;
   int Lq, Lk_max, H;
+  int n_qtiles, n_units;   // query tiles per (group, head) unit; units = groups * heads
+  int spread;              // few units: spread a unit's query tiles over the XCDs
   int use_kv_len;
   int kv_len[64];
   float scale_log2;  // log2(e) / sqrt(dh)
@@ -59,23 +70,22 @@ template <int DH>
 struct Cfg {
   static constexpr int KS = (DH + 15) / 16;        // k-steps of Q K^T
   static constexpr int DCH = DH / 8;               // 16-byte chunks per K/V row
-  static constexpr int KROW = DCH * 16;            // K row pitch in LDS: packed
+  static constexpr int KROW = DCH * 16;            // K/V row pitch in LDS: packed
   static constexpr bool SWZ = (KROW % 128) == 0;   // packed pitch would alias banks: swizzle chunks
   static constexpr bool ONES = (DH % 32) != 0;     // a spare V^T row exists for the row sum
   static constexpr int DT = (DH + 31) / 32;        // 32-row tiles of V^T
-  static constexpr int VROW = KT * 2 + 16;         // V^T row pitch (bytes)
-  static constexpr int K_BYTES = KT * KROW;
-  static constexpr int V_BYTES = DT * 32 * VROW;
-  static constexpr int STAGE = K_BYTES + V_BYTES;
-  static constexpr int K_INSTR = K_BYTES / 1024;   // wave-wide 16-byte direct loads per K tile
-  static_assert(K_BYTES % 1024 == 0, "K tile must be a whole number of wave loads");
+  static constexpr int T_BYTES = KT * KROW;        // one K or V tile
+  static constexpr int STAGE = 2 * T_BYTES;        // K tile, then V tile
+  static constexpr int OVERRUN = 64;               // V^T rows past the head dim read up to this far past a tile
+  static constexpr int T_INSTR = T_BYTES / 1024;   // wave-wide 16-byte direct loads per tile
+  static_assert(T_BYTES % 1024 == 0, "a tile must be a whole number of wave loads");
+  static_assert((DT * 32 - DH) * 2 <= OVERRUN, "overrun of the padded V^T rows");
 };
 
-// position of key offset o (0..15) inside its group of 16 in the V^T rows:
-// o = 8 g + 4 h + e  ->  8 h + 4 g + e   (h: lane half, g: accumulator group parity)
-__device__ __forceinline__ int key_pos16(int o) { return ((o & 4) << 1) | ((o & 8) >> 1) | (o & 3); }
-
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+template <bool V>
+struct BoolTag { static constexpr bool value = V; };
 
 template <int DH>
 __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
@@ -83,12 +93,27 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lh = lane >> 5;
-  const int h = blockIdx.y, g = blockIdx.z;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  All query tiles of a
+  // (group, head) unit read the same K/V, so a unit lives on ONE XCD: unit u on XCD u % 8, its
+  // query tiles consecutive there.
+  // (With only a few units that would leave XCDs idle; their K/V are then small enough for every
+  // L2, and consecutive workgroups simply take consecutive query tiles.)
+  int unit, qtile;
+  if (p.spread) {
+    unit = blockIdx.x / p.n_qtiles;
+    qtile = blockIdx.x - unit * p.n_qtiles;
+  } else {
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    unit = (idx / p.n_qtiles) * 8 + xcd;
+    qtile = idx % p.n_qtiles;
+  }
+  if (unit >= p.n_units) return;
+  const int h = unit % p.H, g = unit / p.H;
   const int g_out = g / p.g_inner, g_in = g - g_out * p.g_inner;
   const int Lk = p.use_kv_len ? p.kv_len[g_out] : p.Lk_max;
   const int64_t q_tok0 = p.q_outer * g_out + p.q_inner * g_in;
   const int64_t kv_tok0 = p.kv_outer * g_out + p.kv_inner * g_in;
-  const int q0 = blockIdx.x * QT + wave * 32;
+  const int q0 = qtile * QT + wave * 32;
   const bf16_t *kbase = p.k + kv_tok0 * p.ld_kv + h * DH;
   const bf16_t *vbase = p.v + kv_tok0 * p.ld_kv + h * DH;
   const int64_t kv_row = p.kv_tok_step * p.ld_kv;   // elements between consecutive keys
@@ -108,79 +133,63 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
     }
   }
 
-  // ---- V^T padding rows (DH .. 32 DT - 1) of both stages: zero, except the row of ones
-  if constexpr (C::DT * 32 > DH) {
-    constexpr int PER_STAGE = (C::DT * 32 - DH) * (KT / 2);   // 32-bit words
-    for (int i = tid; i < 2 * PER_STAGE; i += 256) {
-      const int st = i / PER_STAGE, rem = i % PER_STAGE;
-      const int row = DH + rem / (KT / 2), w = rem % (KT / 2);
-      const uint32_t val = (C::ONES && row == DH) ? 0x3F803F80u : 0u;  // bf16 1.0 twice
-      *reinterpret_cast<uint32_t *>(smem + st * C::STAGE + C::K_BYTES + row * C::VROW + w * 4) = val;
-    }
-  }
-
-  // ---- K tile, global -> LDS: wave-wide load j fills LDS bytes [1024 j, 1024 j + 1024) of the tile;
-  // this lane's piece is LDS chunk m = 64 j + lane = (key m / DCH, chunk slot m % DCH)
-  constexpr int KJ = (C::K_INSTR + 3) / 4;   // loads per wave (the last one only on some waves)
-  int k_key[KJ], k_col[KJ];
+  // ---- K and V tiles, global -> LDS: wave-wide load j fills LDS bytes [1024 j, 1024 j + 1024) of a
+  // tile; this lane's piece is LDS chunk m = 64 j + lane = (key m / DCH, chunk slot m % DCH)
+  constexpr int TJ = (C::T_INSTR + 3) / 4;   // loads per wave and tile (the last one only on some waves)
+  int t_key[TJ], t_col[TJ];
 #pragma unroll
-  for (int i = 0; i < KJ; ++i) {
+  for (int i = 0; i < TJ; ++i) {
     const int m = 64 * (wave + 4 * i) + lane;
     const int key = m / C::DCH, slot = m - key * C::DCH;
-    k_key[i] = key;
-    k_col[i] = (C::SWZ ? (slot ^ (key & 7)) : slot) * 8;
+    t_key[i] = key;
+    t_col[i] = (C::SWZ ? (slot ^ (key & 7)) : slot) * 8;
   }
-  // ---- V tile through registers: task A (every lane): key pair kp = l32, chunk 2 wave + lh;
-  // task B (dh 72 only: the 9th chunk): lanes 0..31 of wave (tile & 3)
-  constexpr bool VB = (C::DCH % 8) != 0;
-  const int v_pos = ((2 * l32) & ~15) | key_pos16((2 * l32) & 15);   // even: the pair stays adjacent
-  uint4 va0, va1, vb0, vb1;
-  va0 = va1 = vb0 = vb1 = make_uint4(0u, 0u, 0u, 0u);
+  // offsets of this lane's pieces in tile 0; a full tile t is fetched at + t * KT keys, a tile that
+  // overhangs the sequence takes the slow path (its keys are clamped, and masked later)
+  int64_t t_off[TJ];
+#pragma unroll
+  for (int i = 0; i < TJ; ++i) t_off[i] = t_key[i] * kv_row + t_col[i];
 
-#define FA_LOAD_TILE(KEY0, STAGE_IDX, TILE_IDX)                                                         \
+  // one operand (K: WHICH = 0, V: WHICH = 1) of the tile starting at key KEY0 -> stage STAGE_IDX
+#define FA_LOAD(WHICH, KEY0, STAGE_IDX, TILE_IDX)                                                       \
   do {                                                                                                  \
-    _Pragma("unroll") for (int i = 0; i < KJ; ++i) {                                                    \
-      if (wave + 4 * i < C::K_INSTR) {                                                                  \
-        int key_ = (KEY0) + k_key[i];                                                                   \
-        if (key_ > Lk - 1) key_ = Lk - 1; /* tail keys re-read the last valid key; masked below */      \
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kbase + key_ * kv_row + k_col[i]),                 \
-                                         (lds_ptr_t)(smem + (STAGE_IDX) * C::STAGE + (wave + 4 * i) * 1024), \
-                                         16, 0, 0);                                                     \
+    unsigned char *dst_ = smem + (STAGE_IDX) * C::STAGE + (WHICH) * C::T_BYTES;                         \
+    const bf16_t *src_ = (WHICH) ? vbase : kbase;                                                       \
+    if ((KEY0) + KT <= Lk) {                                                                            \
+      const int64_t toff_ = (int64_t)(TILE_IDX) * KT * kv_row;                                          \
+      _Pragma("unroll") for (int i = 0; i < TJ; ++i) {                                                  \
+        if (wave + 4 * i < C::T_INSTR)                                                                  \
+          __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_ + t_off[i] + toff_),                        \
+                                           (lds_ptr_t)(dst_ + (wave + 4 * i) * 1024), 16, 0, 0);        \
+      }                                                                                                 \
+    } else {                                                                                            \
+      _Pragma("unroll") for (int i = 0; i < TJ; ++i) {                                                  \
+        if (wave + 4 * i < C::T_INSTR) {                                                                \
+          int key_ = (KEY0) + t_key[i];                                                                 \
+          if (key_ > Lk - 1) key_ = Lk - 1; /* tail keys re-read the last valid key; masked below */    \
+          __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_ + key_ * kv_row + t_col[i]),                \
+                                           (lds_ptr_t)(dst_ + (wave + 4 * i) * 1024), 16, 0, 0);        \
+        }                                                                                               \
       }                                                                                                 \
     }                                                                                                   \
-    {                                                                                                   \
-      int ka_ = (KEY0) + 2 * l32, kb_ = ka_ + 1;                                                        \
-      if (ka_ > Lk - 1) ka_ = Lk - 1;                                                                   \
-      if (kb_ > Lk - 1) kb_ = Lk - 1;                                                                   \
-      const int dc_ = 2 * wave + lh;                                                                    \
-      va0 = *reinterpret_cast<const uint4 *>(vbase + ka_ * kv_row + dc_ * 8);                           \
-      va1 = *reinterpret_cast<const uint4 *>(vbase + kb_ * kv_row + dc_ * 8);                           \
-      if (VB && wave == ((TILE_IDX) & 3) && lh == 0) {                                                  \
-        vb0 = *reinterpret_cast<const uint4 *>(vbase + ka_ * kv_row + 64);                              \
-        vb1 = *reinterpret_cast<const uint4 *>(vbase + kb_ * kv_row + 64);                              \
-      }                                                                                                 \
-    }                                                                                                   \
   } while (0)
 
-#define FA_VT_WRITE(DST, A, B)                                                                          \
-  do {                                                                                                  \
-    unsigned char *d_ = (DST);                                                                          \
-    *reinterpret_cast<uint32_t *>(d_ + 0 * C::VROW) = ((A).x & 0xFFFFu) | ((B).x << 16);               \
-    *reinterpret_cast<uint32_t *>(d_ + 1 * C::VROW) = ((A).x >> 16) | ((B).x & 0xFFFF0000u);           \
-    *reinterpret_cast<uint32_t *>(d_ + 2 * C::VROW) = ((A).y & 0xFFFFu) | ((B).y << 16);               \
-    *reinterpret_cast<uint32_t *>(d_ + 3 * C::VROW) = ((A).y >> 16) | ((B).y & 0xFFFF0000u);           \
-    *reinterpret_cast<uint32_t *>(d_ + 4 * C::VROW) = ((A).z & 0xFFFFu) | ((B).z << 16);               \
-    *reinterpret_cast<uint32_t *>(d_ + 5 * C::VROW) = ((A).z >> 16) | ((B).z & 0xFFFF0000u);           \
-    *reinterpret_cast<uint32_t *>(d_ + 6 * C::VROW) = ((A).w & 0xFFFFu) | ((B).w << 16);               \
-    *reinterpret_cast<uint32_t *>(d_ + 7 * C::VROW) = ((A).w >> 16) | ((B).w & 0xFFFF0000u);           \
-  } while (0)
-
-#define FA_STORE_V(STAGE_IDX, TILE_IDX)                                                                 \
-  do {                                                                                                  \
-    unsigned char *sv_ = smem + (STAGE_IDX) * C::STAGE + C::K_BYTES + v_pos * 2;                        \
-    FA_VT_WRITE(sv_ + (2 * wave + lh) * 8 * C::VROW, va0, va1);                                         \
-    if (VB && wave == ((TILE_IDX) & 3) && lh == 0) FA_VT_WRITE(sv_ + 64 * C::VROW, vb0, vb1);           \
-  } while (0)
+  // ---- V^T operand addressing (ds_read_b64_tr_b16).  For contraction chunk kc and row tile dt this
+  // lane (d = 32 dt + l32, key half lh) needs keys 16 kc + 4 lh + {0..3} and 16 kc + 8 + 4 lh + {0..3}.
+  // Inside its 16-lane block (d base 32 dt + 16 (l32 / 16)) lane i supplies the piece of key
+  // (i / 4) at d-group (i % 4).
+  const int tr_key = 4 * lh + ((lane & 15) >> 2);                 // + 16 kc (+ 8 for the second read)
+  const int tr_d = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);       // + 32 dt
+  int tr_off[C::DT][2];   // byte offset inside a V tile for kc = 0, first / second read
+#pragma unroll
+  for (int dt = 0; dt < C::DT; ++dt)
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const int key = tr_key + 8 * hf, d = 32 * dt + tr_d;
+      const int chunk = d >> 3;
+      // past the packed row (d >= DH) the address simply runs on into the next key's row
+      tr_off[dt][hf] = C::SWZ ? key * C::KROW + (((chunk ^ (key & 7)) << 4) | ((d & 7) << 1)) : key * C::KROW + d * 2;
+    }
 
   floatx16 oacc[C::DT];
 #pragma unroll
@@ -190,68 +199,80 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
   float m_run = -INFINITY;   // running maximum of the raw (unscaled) scores of this lane's query
   float l_run = 0.f;         // running sum (only used when there is no ones row)
 
-  const int n_tiles = (Lk + KT - 1) / KT;
-  FA_LOAD_TILE(0, 0, 0);
-  FA_STORE_V(0, 0);
-  if (n_tiles > 1) FA_LOAD_TILE(KT, 1, 1);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // K of tile 0 has landed (once per kernel: also waits tile 1)
-  lds_barrier();
+  // S^T = K Q^T for the 64 keys of the tile in stage STAGE_IDX (prologue only).  Past the head dim
+  // the Q fragment is zero, so any finite K data will do there: the K chunk index is clamped
+  // instead of branching.
+#define FA_QK(SREG, STAGE_IDX)                                                                          \
+  do {                                                                                                  \
+    const unsigned char *sk_ = smem + (STAGE_IDX) * C::STAGE;                                           \
+    _Pragma("unroll") for (int kt = 0; kt < 2; ++kt) {                                                  \
+      _Pragma("unroll") for (int e = 0; e < 16; ++e) SREG[kt][e] = 0.f;                                 \
+      const int row_ = kt * 32 + l32;                                                                   \
+      _Pragma("unroll") for (int ks = 0; ks < C::KS; ++ks) {                                            \
+        const int c_ = 2 * ks + lh < C::DCH ? 2 * ks + lh : C::DCH - 1;                                 \
+        const bf16x8 kf_ =                                                                              \
+            *reinterpret_cast<const bf16x8 *>(sk_ + row_ * C::KROW + (C::SWZ ? (c_ ^ (row_ & 7)) : c_) * 16); \
+        SREG[kt] = mfma32(kf_, qf[ks], SREG[kt]);                                                       \
+      }                                                                                                 \
+    }                                                                                                   \
+  } while (0)
 
-  for (int it = 0; it < n_tiles; ++it) {
-    const int cur = it & 1;
-    const unsigned char *sk = smem + cur * C::STAGE;
-    const unsigned char *sv = sk + C::K_BYTES;
+#define FENCE() __builtin_amdgcn_sched_barrier(0)
 
-    // ---- S^T = K Q^T for the 64 keys of this tile
-    floatx16 s[2];
+  floatx16 s_a[2], s_b[2];   // scores of the current / next tile, swapping roles every tile
+
+  // One key tile: online softmax of s_cur (tile it) and O^T += V^T P^T, with -- when there is a next
+  // tile -- the MFMAs of its scores s_nxt = K Q^T threaded through the softmax arithmetic.  The
+  // instruction order is written out by hand and fenced: a wavefront issues in order, so each MFMA
+  // (32 clocks in the matrix core, dependent on the one two slots earlier) is followed by a slice
+  // of VALU work that does not depend on it; the exponentials of tile it and the MFMAs of both
+  // products then run side by side instead of one after the other.
+  auto tile_step = [&](auto next_tag, int cur, floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2]) {
+    constexpr bool NEXT = decltype(next_tag)::value;
+    constexpr int NQ = NEXT ? 2 * C::KS : 0;      // MFMAs of the next tile's scores
+    constexpr int NPV = 4 * C::DT;                // MFMAs of this tile's O update
+    constexpr int M = NQ + NPV;
+    const unsigned char *sk = smem + (cur ^ 1) * C::STAGE;            // K of tile it+1
+    const unsigned char *sv = smem + cur * C::STAGE + C::T_BYTES;     // V of tile it
+    bf16x8 kf[NEXT ? NQ : 1];
+    if constexpr (NEXT) {
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) s[kt][e] = 0.f;
-      const int row = kt * 32 + l32;
-#pragma unroll
-      for (int ks = 0; ks < C::KS; ++ks) {
-        const int c = 2 * ks + lh;
-        bf16x8 kf;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) kf[e] = (bf16_t)0.f;
-        if (c < C::DCH)
-          kf = *reinterpret_cast<const bf16x8 *>(sk + row * C::KROW + (C::SWZ ? (c ^ (row & 7)) : c) * 16);
-        s[kt] = mfma32(kf, qf[ks], s[kt]);
+      for (int q = 0; q < NQ; ++q) {              // slot q: key half q & 1, k-step q >> 1
+        const int row = (q & 1) * 32 + l32;
+        const int c = 2 * (q >> 1) + lh < C::DCH ? 2 * (q >> 1) + lh : C::DCH - 1;
+        kf[q] = *reinterpret_cast<const bf16x8 *>(sk + row * C::KROW + (C::SWZ ? (c ^ (row & 7)) : c) * 16);
       }
     }
-    // ---- mask the keys past the end (last tile only)
-    const int key0 = it * KT;
-    if (key0 + KT > Lk) {
+    FENCE();
+    floatx16 zero16;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+    for (int e = 0; e < 16; ++e) zero16[e] = 0.f;
+#define FA_SLOT_QK(Q)                                                                                   \
+  do {                                                                                                  \
+    if constexpr (NEXT) s_nxt[(Q) & 1] = mfma32(kf[Q], qf[(Q) >> 1], (Q) < 2 ? zero16 : s_nxt[(Q) & 1]); \
+  } while (0)
+    // ---- row maximum of the raw scores
+    FA_SLOT_QK(0);
+    FENCE();
+    float mx = s_cur[0][0];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-          if (key >= Lk) s[kt][r] = -INFINITY;
-        }
-    }
-    // ---- online softmax for this lane's query
-    float mx = s[0][0];
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_cur[0][r]);
+    FENCE();
+    FA_SLOT_QK(1);
+    FENCE();
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_cur[1][r]);
+    const float mx_other = __shfl_xor(mx, 32, 64);
+    FENCE();
+    FA_SLOT_QK(2);
+    FENCE();
+    FA_SLOT_QK(3);
+    FENCE();
+    const float m_new = fmaxf(m_run, fmaxf(mx, mx_other));
     const float mb = m_new * p.scale_log2;
-    bf16x8 pf[4];
-    float psum = 0.f;
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pv = __builtin_amdgcn_exp2f(s[kt][r] * p.scale_log2 - mb);
-        const bf16_t pb = (bf16_t)pv;
-        pf[kt * 2 + (r >> 3)][r & 7] = pb;
-        if (!C::ONES) psum += (float)pb;
-      }
-    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // some query of the wave has a new maximum
+    FENCE();
+    // ---- O (and the running sum) are rescaled when some query of the wavefront has a new maximum
+    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2);
 #pragma unroll
       for (int d = 0; d < C::DT; ++d)
@@ -260,26 +281,130 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
       if (!C::ONES) l_run *= alpha;
       m_run = m_new;
     }
-    if (!C::ONES) l_run += psum;
-
-    // ---- O^T += V^T P^T
+    bf16x8 vf[NPV];   // V^T fragments, slot v = kc * DT + d; read three pairs ahead of their first use
+    FENCE();
+    // ---- exponentials two at a time; after each pair the next MFMA slot: the rest of the next
+    // tile's scores first, then the O update, whose slot (kc, d) needs the 8 kc + 8 first
+    // probabilities, i.e. pair 4 kc + 3
+    bf16x8 pf[4];
+    float psum = 0.f;
+    int slot = NEXT ? 4 : 0;
 #pragma unroll
-    for (int kc = 0; kc < 4; ++kc) {
+    for (int g = 0; g < 16; ++g) {
+      if (g % 3 == 0 && g / 3 < 4) {
+        const int kc = g / 3;
 #pragma unroll
-      for (int d = 0; d < C::DT; ++d) {
-        const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(sv + (d * 32 + l32) * C::VROW + (2 * kc + lh) * 16);
-        oacc[d] = mfma32(vf, pf[kc], oacc[d]);
+        for (int d = 0; d < C::DT; ++d) {
+          const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s4_ptr_t)(sv + tr_off[d][0] + kc * 16 * C::KROW));
+          const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s4_ptr_t)(sv + tr_off[d][1] + kc * 16 * C::KROW));
+          typedef short shortx8 __attribute__((ext_vector_type(8)));
+          shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          if (C::ONES && d == DH / 32 && l32 == DH % 32) {   // the row of ones: sum of the probabilities
+#pragma unroll
+            for (int e = 0; e < 8; ++e) both[e] = (short)0x3F80;
+          }
+          vf[kc * C::DT + d] = __builtin_bit_cast(bf16x8, both);
+        }
+      }
+#pragma unroll
+      for (int e = 2 * g; e < 2 * g + 2; ++e) {
+        const bf16_t pb = (bf16_t)__builtin_amdgcn_exp2f(s_cur[e >> 4][e & 15] * p.scale_log2 - mb);
+        pf[e >> 3][e & 7] = pb;
+        if (!C::ONES) psum += (float)pb;
+      }
+      FENCE();
+      if (slot < NQ) {
+        FA_SLOT_QK(slot);
+        ++slot;
+      } else if (slot < M) {
+        const int v = slot - NQ, kc = v / C::DT, d = v - kc * C::DT;
+        if (g >= 4 * kc + 3) {
+          oacc[d] = mfma32(vf[v], pf[kc], oacc[d]);
+          ++slot;
+        }
+      }
+      FENCE();
+    }
+#pragma unroll
+    for (int sl = 0; sl < M; ++sl) {
+      if (sl >= slot) {
+        if (sl < NQ) {
+          FA_SLOT_QK(sl);
+        } else {
+          const int v = sl - NQ, kc = v / C::DT, d = v - kc * C::DT;
+          oacc[d] = mfma32(vf[v], pf[kc], oacc[d]);
+        }
       }
     }
+    if (!C::ONES) l_run += psum;
+#undef FA_SLOT_QK
+  };
 
-    if (it + 1 < n_tiles) FA_STORE_V(cur ^ 1, it + 1);           // registers hold V of tile it+1
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");             // K of tile it+1 has landed
-    lds_barrier();                                               // stage cur is free, stage cur^1 complete
-    if (it + 2 < n_tiles) FA_LOAD_TILE((it + 2) * KT, cur, it + 2);
+  // Software pipeline over the key tiles.  Stage it & 1 holds K and V of tile it.  K of tile it is
+  // dead once its scores exist (formed during tile it-1), so K of tile it+2 is fetched at the start
+  // of tile it; V of tile it is used until the end of tile it, so V of tile it+2 follows after the
+  // barrier that ends tile it.  Both have a whole tile's time to land.
+  const int n_tiles = (Lk + KT - 1) / KT;
+  FA_LOAD(0, 0, 0, 0);
+  FA_LOAD(1, 0, 0, 0);
+  if (n_tiles > 1) {
+    FA_LOAD(0, KT, 1, 1);
+    FA_LOAD(1, KT, 1, 1);
   }
-#undef FA_LOAD_TILE
-#undef FA_VT_WRITE
-#undef FA_STORE_V
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // tile 0 has landed (once per kernel: also waits tile 1)
+  lds_barrier();
+  FA_QK(s_a, 0);
+  lds_barrier();                                      // K of tile 0 may now be overwritten (by tile 2)
+
+#define FA_ITER(HAS_NEXT, S_CUR, S_NXT)                                                                 \
+  do {                                                                                                  \
+    const int cur_ = it & 1;                                                                            \
+    if (it + 2 < n_tiles) FA_LOAD(0, (it + 2) * KT, cur_, it + 2);                                      \
+    FENCE();                                                                                            \
+    tile_step(BoolTag<HAS_NEXT>{}, cur_, S_CUR, S_NXT);                                                 \
+    FENCE();                                                                                            \
+    if (HAS_NEXT) {                                                                                     \
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K of tile it+2 (and V of tile it+1) has landed */ \
+      lds_barrier(); /* V of tile it, K of tile it+1 are free; tile it+1's V and tile it+2's K complete */ \
+      if (it + 2 < n_tiles) FA_LOAD(1, (it + 2) * KT, cur_, it + 2);                                    \
+    }                                                                                                   \
+  } while (0)
+
+  int it = 0;
+  for (; it + 2 < n_tiles; it += 2) {
+    FA_ITER(true, s_a, s_b);
+    ++it;
+    FA_ITER(true, s_b, s_a);
+    --it;
+  }
+  // ---- one or two tiles left; the last one masks the keys past the end
+  auto mask_tail = [&](floatx16 (&sc)[2]) {
+    const int key0 = it * KT;
+    if (key0 + KT > Lk) {
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          if (key >= Lk) sc[kt][r] = -INFINITY;
+        }
+    }
+  };
+  if (it + 1 < n_tiles) {
+    FA_ITER(true, s_a, s_b);
+    ++it;
+    mask_tail(s_b);
+    FA_ITER(false, s_b, s_a);
+  } else {
+    mask_tail(s_a);
+    FA_ITER(false, s_a, s_b);
+  }
+#undef FA_ITER
+#undef FENCE
+#undef FA_QK
+#undef FA_LOAD
 
   // ---- row sum
   float l_tot;
@@ -314,7 +439,7 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
 template <int DH>
 int launch_dh(const FlashParams &p, int n_groups, hipStream_t s) {
   using C = Cfg<DH>;
-  constexpr int smem = 2 * C::STAGE;
+  constexpr int smem = 2 * C::STAGE + C::OVERRUN;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_flash_attn<DH>),
@@ -322,8 +447,9 @@ int launch_dh(const FlashParams &p, int n_groups, hipStream_t s) {
     if (e != hipSuccess) return ddit::hip_fail(e, "flash hipFuncSetAttribute");
     attr_set = true;
   }
-  dim3 grid((unsigned)((p.Lq + QT - 1) / QT), (unsigned)p.H, (unsigned)n_groups);
-  hipLaunchKernelGGL(k_flash_attn<DH>, grid, dim3(256), smem, s, p);
+  const int64_t blocks = (p.spread ? (int64_t)p.n_units : (int64_t)((p.n_units + 7) / 8) * 8) * p.n_qtiles;
+  if (blocks > 0x7fffffff) { ddit::set_error("attention: too many workgroups"); return -2; }
+  hipLaunchKernelGGL(k_flash_attn<DH>, dim3((unsigned)blocks), dim3(256), smem, s, p);
   return ddit::hip_fail(hipGetLastError(), "flash attention launch");
 }
 
@@ -348,10 +474,13 @@ int launch_flash_attn(const AttnArgs &a, hipStream_t s) {
   for (int i = 0; i < 64; ++i) p.kv_len[i] = a.kv_len[i];
   p.scale = 1.0f / sqrtf((float)a.dh);
   p.scale_log2 = p.scale * 1.4426950408889634f;
-  if (a.n_groups > 65535 || a.H > 65535) {
+  if ((int64_t)a.n_groups * a.H > 0x3fffffff) {
     set_error("attention grid too large (groups=%d heads=%d)", a.n_groups, a.H);
     return -2;
   }
+  p.n_qtiles = (a.Lq + QT - 1) / QT;
+  p.n_units = a.n_groups * a.H;
+  p.spread = p.n_units < 64;
   if (a.dh == 72) return launch_dh<72>(p, a.n_groups, s);
   if (a.dh == 64) return launch_dh<64>(p, a.n_groups, s);
   set_error("dh=%d: supported head dims are 64 and 72", a.dh);
