@@ -39,6 +39,21 @@ def step_flops(sh, valid):
             "temporal": temporal, "cross": cross, "fc1": lin(N, M, D)}
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the fc1 GEMM as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two
+    runs, scaled by what the same counters read for the step's own streaming cast kernels of known
+    size); the figure is kept, with the commands that produced it, in profiles/.  None if not measured
+    for this workload."""
+    path = os.path.join(ROOT, "profiles", "gemm_fc1_gelu_%s_hbm_traffic.txt" % WORKLOAD_NAMES[workload])
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -125,9 +140,10 @@ def main():
         reps = max(args.steps, 5)
         ms = time_call(lambda: m.ddit_linear_fwd(m.DDIT_EPI_GELU_BF16, xh, D, lw["w_fc1"], lw["b_fc1"], N, M, D, h, M), reps)
         tf = fl["fc1"] / (ms * 1e-3) / 1e12
-        roofline = {"kernel": "k_gemm_bf16<256,192,GELU> (MLP fc1, %dx%dx%d)" % (N, M, D), "bound": "mfma",
-                    "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(tf / PEAK_BF16_TFLOPS, 4), "ms_per_launch": round(ms, 4), "traffic": None}
+        roofline = {"kernel": "k_gemm_bf16<2,4,3,3,4,1> = 192x384 tiles, GELU epilogue (MLP fc1, %dx%dx%d)" % (N, M, D),
+                    "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tf / PEAK_BF16_TFLOPS, 4), "ms_per_launch": round(ms, 4),
+                    "traffic": measured_traffic(args.workload)}
         stages["fc1_gelu"] = {"ms": round(ms, 4), "tflops": round(tf, 1), "frac_mfma": round(tf / PEAK_BF16_TFLOPS, 4)}
         qkv = torch.randn(N, 3 * A, device="cuda").to(torch.bfloat16)
         o = torch.empty(N, A, dtype=torch.bfloat16, device="cuda")

@@ -616,8 +616,10 @@ int launch_one(const GemmParams &p0, hipStream_t s) {
   const int64_t tiles_m = (p.N + C::BM - 1) / C::BM;
   p.tiles_m = (int)tiles_m;
   p.tiles_n = (p.n + C::BN - 1) / C::BN;
-  // width of an out-feature group: at most 8 tiles, as even as the tile count allows
-  const int n_groups = (p.tiles_n + 7) / 8;
+  // width of an out-feature group: at most 4 tiles (their W, about 3.5 MB at k = 1152, stays in an
+  // XCD's 4 MB L2 next to the token panels streaming through), as even as the tile count allows
+  const int max_w = 4;
+  const int n_groups = (p.tiles_n + max_w - 1) / max_w;
   p.group_w = (p.tiles_n + n_groups - 1) / n_groups;
   const int64_t total = tiles_m * p.tiles_n;
   if (total > (int64_t)1 << 30) {
