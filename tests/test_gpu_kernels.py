@@ -58,7 +58,13 @@ LIN_CASES = [
     (777, 4608, 1152),    # fc1 shape, ragged token tail, several tiles
     (515, 1152, 4608),    # fc2 shape
     (130, 864, 1152),     # n not a multiple of the tile
-    (1, 8, 8),
+    (130, 864, 1160),     # k tail (k % 32 == 8) on the small tile
+    (1, 8, 8),            # a single partial k-step
+    (40, 64, 72),         # two full k-steps and a tail: fewer steps than the pipeline is deep
+    # the large tile (192 x 384, eight wavefronts) needs >= 128 tiles:
+    (8200, 1152, 288),    # narrow attention width as k, ragged token tail, tiles over two samples
+    (5000, 4608, 1160),   # k tail on the large tile
+    (4100, 2440, 512),    # n not a multiple of 384: ragged last out-feature tile
 ]
 
 
