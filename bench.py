@@ -195,7 +195,8 @@ def main():
                          "frames x%d layers to a full step" % (Ts, sh.T, shs.N, dt, sh.T / Ts, layers)}
 
     out = {
-        "metric": "DiT denoise-step latency (ms) at 480p-shaped latents; attention TFLOP/s in 'stages'",
+        "metric": "DiT denoise-step latency (ms) at %s-shaped latents; attention TFLOP/s in 'stages'" %
+                  WORKLOAD_NAMES[args.workload].split("-")[0],
         "value": round(ms_per_step, 3), "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",

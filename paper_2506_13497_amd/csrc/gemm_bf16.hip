@@ -646,10 +646,14 @@ int launch_one(const GemmParams &p0, hipStream_t s) {
 
 template <int EPI>
 int launch_epi(const GemmParams &p, hipStream_t s) {
-  // 384-wide feature tiles divide 1152, 3456 and 4608 exactly; narrow outputs and short token
-  // counts take the small tile so that more than a handful of CUs get work.
-  const int64_t big_tiles = ((p.N + 191) / 192) * ((p.n + 383) / 384);
-  const bool big = big_tiles >= 128 && p.n >= 384 && (p.n % 384 == 0 || p.n > 2048);
+  // The 192x384 tile runs at roughly twice the rate of the small one per useful flop, so it is
+  // taken whenever there are enough tiles to fill half the chip and at most 30 % of the
+  // 384-wide feature tiles is padding (288 and 864 out-features qualify; 384-wide tiles divide
+  // 1152, 3456 and 4608 exactly).  Narrow outputs and short token counts take the small tile so
+  // that more than a handful of CUs get work.
+  const int64_t tiles_n = (p.n + 383) / 384;
+  const int64_t big_tiles = ((p.N + 191) / 192) * tiles_n;
+  const bool big = big_tiles >= 128 && 10 * (int64_t)p.n >= 7 * 384 * tiles_n;
   return big ? launch_one<2, 4, 3, 3, 4, EPI>(p, s) : launch_one<2, 2, 2, 2, 4, EPI>(p, s);
 }
 
