@@ -24,19 +24,27 @@
 // each lane of a 16-lane block four KEYS' values of its own d (lane i of the block
 // supplies the address of the 8-byte piece "key i/4, d-group i%4"; it receives element i%4
 // of the pieces of lanes i/4, 4+i/4, 8+i/4, 12+i/4), two such reads per operand.
-// The head dim 72 is padded to 80 for Q K^T (zero Q in registers) and to 96 rows for V^T
+// The head dim is padded to the next multiple of 16 above it for Q K^T and to 96 rows for V^T
 // (rows past the head dim read neighbouring data and produce rows of O^T that are never
 // stored); the lanes of row 72 substitute ones, so that the same MFMAs that form O also
 // accumulate the softmax denominator (of the bf16-rounded probabilities used).
+//
+// Online softmax without per-score bookkeeping.  The first padding column of the contraction
+// (index dh) is put to work: K holds a one there (a constant 16-byte piece in LDS that the lanes
+// of that column read instead of tile data) and Q holds minus the query's reference score, so the
+// matrix core delivers s - m_ref directly and a probability is one multiply (by log2(e)/sqrt(dh))
+// and one exponential.  m_ref is set from the first key tile and moved later only if a score
+// exceeds it by 8 binary orders of magnitude; only then are O and the pending scores rescaled.
+// Any reference gives the same softmax as long as every term uses the same one.
 //
 // Data movement.  K and V tiles go global -> LDS directly (16 bytes per lane, no
 // registers), packed at a 144-byte row pitch for dh 72 or at 128 bytes with an XOR chunk
 // swizzle for dh 64.  Two stages; the next tile's loads are in flight during the current
 // tile's arithmetic; one barrier per tile.
 //
-// Instruction order.  The inner loop is bound by the vector ALU (one exponential per
-// score is a quarter-rate instruction), so the MFMAs are threaded through it by hand: see
-// tile_step.
+// Instruction order.  Per key tile a wavefront has about as many vector-ALU clocks (one
+// exponential per score is a half-rate instruction) as matrix-core clocks, so the MFMAs are
+// threaded through the exponentials by hand: see tile_step.
 #include "ddit_common.hpp"
 
 namespace {
@@ -64,23 +72,40 @@ struct FlashParams {
   int kv_len[64];
   float scale_log2;  // log2(e) / sqrt(dh)
   float scale;       // 1 / sqrt(dh)
+  float rebase;      // 8 / scale_log2: a score this far above its query's reference moves the reference
 };
 
 template <int DH>
 struct Cfg {
-  static constexpr int KS = (DH + 15) / 16;        // k-steps of Q K^T
+  static constexpr int KS = DH / 16 + 1;           // k-steps of Q K^T: the head dim plus the reference column (index DH)
   static constexpr int DCH = DH / 8;               // 16-byte chunks per K/V row
   static constexpr int KROW = DCH * 16;            // K/V row pitch in LDS: packed
   static constexpr bool SWZ = (KROW % 128) == 0;   // packed pitch would alias banks: swizzle chunks
   static constexpr bool ONES = (DH % 32) != 0;     // a spare V^T row exists for the row sum
   static constexpr int DT = (DH + 31) / 32;        // 32-row tiles of V^T
   static constexpr int T_BYTES = KT * KROW;        // one K or V tile
-  static constexpr int STAGE = 2 * T_BYTES;        // K tile, then V tile
+  static constexpr int KCONST = 2 * T_BYTES;       // offset of the constant K piece (1, 0, ..., 0) in a stage
   static constexpr int OVERRUN = 64;               // V^T rows past the head dim read up to this far past a tile
+  static constexpr int STAGE = 2 * T_BYTES + OVERRUN;   // K tile, V tile, constant piece (the rest of it is slack)
   static constexpr int T_INSTR = T_BYTES / 1024;   // wave-wide 16-byte direct loads per tile
   static_assert(T_BYTES % 1024 == 0, "a tile must be a whole number of wave loads");
   static_assert((DT * 32 - DH) * 2 <= OVERRUN, "overrun of the padded V^T rows");
+  static_assert(DH % 8 == 0, "the reference column starts a 16-byte chunk");
 };
+
+__device__ __forceinline__ unsigned lds_addr(const void *p) {
+  return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
+}
+// Transposing 8-byte LDS read (see the V^T operand below), issued WITHOUT a wait: the result may
+// be used only after lds_wait_* on it.  Written as inline assembly because the compiler, when it
+// sees an LDS read while direct-to-LDS loads are in flight, first waits for ALL of them (it cannot
+// tell that they fill a different stage), which would expose the whole fetch latency every tile.
+template <int IMM>
+__device__ __forceinline__ shortx4 lds_read_tr_nowait(unsigned addr) {
+  shortx4 r;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(IMM));
+  return r;
+}
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
@@ -118,7 +143,9 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
   const bf16_t *vbase = p.v + kv_tok0 * p.ld_kv + h * DH;
   const int64_t kv_row = p.kv_tok_step * p.ld_kv;   // elements between consecutive keys
 
-  // ---- Q fragment: lane holds query l32, d = 16 ks + 8 lh .. +7 (zeros past DH)
+  // ---- Q fragment: lane holds query l32, d = 16 ks + 8 lh .. +7.  Column DH (zero for now) will
+  // carry minus the query's reference score, against a K column of ones; the columns past it stay
+  // zero.
   bf16x8 qf[C::KS];
   {
     int qi = q0 + l32;
@@ -131,6 +158,23 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
       for (int e = 0; e < 8; ++e) qf[ks][e] = (bf16_t)0.f;
       if (d0 < DH) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + d0);
     }
+  }
+  constexpr int KS_REF = DH / 16;                       // k-step of the reference column
+  const bool ref_lane = (8 * lh == DH - 16 * KS_REF);   // lanes whose fragment of that k-step starts at column DH
+
+  // K fragment addressing inside a stage: key (half * 32 + l32), 16-byte chunk 2 ks + lh; the lanes
+  // whose columns lie past the head dim read the constant piece (1, 0, ..., 0) instead
+  int k_off[C::KS][2];
+#pragma unroll
+  for (int ks = 0; ks < C::KS; ++ks)
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) {
+      const int row = hf * 32 + l32, c = 2 * ks + lh;
+      k_off[ks][hf] = c < C::DCH ? row * C::KROW + (C::SWZ ? (c ^ (row & 7)) : c) * 16 : C::KCONST;
+    }
+  if (tid < 2 * (C::OVERRUN / 4)) {   // the constant piece of both stages, and zeros in the slack after it
+    const int st = tid / (C::OVERRUN / 4), w = tid - st * (C::OVERRUN / 4);
+    *reinterpret_cast<unsigned *>(smem + st * C::STAGE + C::KCONST + 4 * w) = w == 0 ? 0x00003F80u : 0u;
   }
 
   // ---- K and V tiles, global -> LDS: wave-wide load j fills LDS bytes [1024 j, 1024 j + 1024) of a
@@ -196,22 +240,22 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
   for (int d = 0; d < C::DT; ++d)
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[d][e] = 0.f;
-  float m_run = -INFINITY;   // running maximum of the raw (unscaled) scores of this lane's query
+  // Scores are taken relative to a per-query reference m_ref (a bf16 value): they come out of the
+  // matrix core as s - m_ref, because column DH of Q holds -m_ref.  The reference is set from the
+  // first tile and afterwards moved only when a score exceeds it by more than p.rebase
+  // (probabilities up to 2^8 are harmless in bf16 and in the fp32 sums), so the common tile needs
+  // neither a subtraction per score nor a rescaling of O.
+  float m_ref = 0.f;
   float l_run = 0.f;         // running sum (only used when there is no ones row)
 
-  // S^T = K Q^T for the 64 keys of the tile in stage STAGE_IDX (prologue only).  Past the head dim
-  // the Q fragment is zero, so any finite K data will do there: the K chunk index is clamped
-  // instead of branching.
+  // S^T = K Q^T for the 64 keys of the tile in stage STAGE_IDX (prologue only)
 #define FA_QK(SREG, STAGE_IDX)                                                                          \
   do {                                                                                                  \
     const unsigned char *sk_ = smem + (STAGE_IDX) * C::STAGE;                                           \
     _Pragma("unroll") for (int kt = 0; kt < 2; ++kt) {                                                  \
       _Pragma("unroll") for (int e = 0; e < 16; ++e) SREG[kt][e] = 0.f;                                 \
-      const int row_ = kt * 32 + l32;                                                                   \
       _Pragma("unroll") for (int ks = 0; ks < C::KS; ++ks) {                                            \
-        const int c_ = 2 * ks + lh < C::DCH ? 2 * ks + lh : C::DCH - 1;                                 \
-        const bf16x8 kf_ =                                                                              \
-            *reinterpret_cast<const bf16x8 *>(sk_ + row_ * C::KROW + (C::SWZ ? (c_ ^ (row_ & 7)) : c_) * 16); \
+        const bf16x8 kf_ = *reinterpret_cast<const bf16x8 *>(sk_ + k_off[ks][kt]);                      \
         SREG[kt] = mfma32(kf_, qf[ks], SREG[kt]);                                                       \
       }                                                                                                 \
     }                                                                                                   \
@@ -227,7 +271,7 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
   // (32 clocks in the matrix core, dependent on the one two slots earlier) is followed by a slice
   // of VALU work that does not depend on it; the exponentials of tile it and the MFMAs of both
   // products then run side by side instead of one after the other.
-  auto tile_step = [&](auto next_tag, int cur, floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2]) {
+  auto tile_step = [&](auto next_tag, bool first, int cur, floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2]) {
     constexpr bool NEXT = decltype(next_tag)::value;
     constexpr int NQ = NEXT ? 2 * C::KS : 0;      // MFMAs of the next tile's scores
     constexpr int NPV = 4 * C::DT;                // MFMAs of this tile's O update
@@ -238,9 +282,7 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
     if constexpr (NEXT) {
 #pragma unroll
       for (int q = 0; q < NQ; ++q) {              // slot q: key half q & 1, k-step q >> 1
-        const int row = (q & 1) * 32 + l32;
-        const int c = 2 * (q >> 1) + lh < C::DCH ? 2 * (q >> 1) + lh : C::DCH - 1;
-        kf[q] = *reinterpret_cast<const bf16x8 *>(sk + row * C::KROW + (C::SWZ ? (c ^ (row & 7)) : c) * 16);
+        kf[q] = *reinterpret_cast<const bf16x8 *>(sk + k_off[q >> 1][q & 1]);
       }
     }
     FENCE();
@@ -251,7 +293,7 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
   do {                                                                                                  \
     if constexpr (NEXT) s_nxt[(Q) & 1] = mfma32(kf[Q], qf[(Q) >> 1], (Q) < 2 ? zero16 : s_nxt[(Q) & 1]); \
   } while (0)
-    // ---- row maximum of the raw scores
+    // ---- largest exponent of the tile (this lane's half of the keys)
     FA_SLOT_QK(0);
     FENCE();
     float mx = s_cur[0][0];
@@ -262,55 +304,94 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
     FENCE();
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_cur[1][r]);
-    const float mx_other = __shfl_xor(mx, 32, 64);
     FENCE();
     FA_SLOT_QK(2);
     FENCE();
     FA_SLOT_QK(3);
     FENCE();
-    const float m_new = fmaxf(m_run, fmaxf(mx, mx_other));
-    const float mb = m_new * p.scale_log2;
-    FENCE();
-    // ---- O (and the running sum) are rescaled when some query of the wavefront has a new maximum
-    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2);
+    // ---- new reference for the queries that need one (always on the first tile): O, the running
+    // sum and this tile's exponents move to it here; the scores of the next tile pick it up from
+    // the Q fragment, whose k-step KS_REF has not been issued yet (slots 2 KS_REF and 2 KS_REF + 1)
+    static_assert(2 * KS_REF >= 4, "the reference column's k-step is issued after the decision");
+    if (__builtin_amdgcn_ballot_w64(first || mx > p.rebase) != 0) {
+      const float mq = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = (first || mq > p.rebase) ? (float)(bf16_t)(m_ref + mq) : m_ref;
+      const float delta = m_new - m_ref;
+      const float alpha = __builtin_amdgcn_exp2f(-delta * p.scale_log2);
 #pragma unroll
       for (int d = 0; d < C::DT; ++d)
 #pragma unroll
         for (int e = 0; e < 16; ++e) oacc[d][e] *= alpha;
       if (!C::ONES) l_run *= alpha;
-      m_run = m_new;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s_cur[kt][e] -= delta;
+      m_ref = m_new;
+      if (ref_lane) qf[KS_REF][0] = (bf16_t)(-m_new);
     }
     bf16x8 vf[NPV];   // V^T fragments, slot v = kc * DT + d; read three pairs ahead of their first use
     FENCE();
     // ---- exponentials two at a time; after each pair the next MFMA slot: the rest of the next
     // tile's scores first, then the O update, whose slot (kc, d) needs the 8 kc + 8 first
     // probabilities, i.e. pair 4 kc + 3
+    shortx4 vlo[NPV], vhi[NPV];
+    const unsigned sv_addr = lds_addr(sv);
+    auto vt_issue = [&](int kc) {      // the six reads of contraction chunk kc (16 keys)
+#pragma unroll
+      for (int d = 0; d < C::DT; ++d) {
+        const int v = kc * C::DT + d;
+        switch (kc) {                  // the key offset is an immediate of the instruction
+          case 0: vlo[v] = lds_read_tr_nowait<0 * 16 * C::KROW>(sv_addr + tr_off[d][0]);
+                  vhi[v] = lds_read_tr_nowait<0 * 16 * C::KROW>(sv_addr + tr_off[d][1]); break;
+          case 1: vlo[v] = lds_read_tr_nowait<1 * 16 * C::KROW>(sv_addr + tr_off[d][0]);
+                  vhi[v] = lds_read_tr_nowait<1 * 16 * C::KROW>(sv_addr + tr_off[d][1]); break;
+          case 2: vlo[v] = lds_read_tr_nowait<2 * 16 * C::KROW>(sv_addr + tr_off[d][0]);
+                  vhi[v] = lds_read_tr_nowait<2 * 16 * C::KROW>(sv_addr + tr_off[d][1]); break;
+          default: vlo[v] = lds_read_tr_nowait<3 * 16 * C::KROW>(sv_addr + tr_off[d][0]);
+                   vhi[v] = lds_read_tr_nowait<3 * 16 * C::KROW>(sv_addr + tr_off[d][1]); break;
+        }
+      }
+    };
+    // Chunk kc has arrived once at most the reads of ONE later chunk are outstanding (LDS reads
+    // return in order; chunk kc + 2 is never issued before chunk kc is used).  The wait names the
+    // registers, so nothing that uses them can move above it.
+    auto vt_ready = [&](int kc) {
+      static_assert(C::DT == 3 || C::DT == 2, "register list of the wait");
+      const int v = kc * C::DT;
+      if (C::DT == 3) {
+        if (kc == 3)
+          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vlo[v]), "+v"(vhi[v]), "+v"(vlo[v + 1]), "+v"(vhi[v + 1]),
+                       "+v"(vlo[v + C::DT - 1]), "+v"(vhi[v + C::DT - 1]));
+        else
+          asm volatile("s_waitcnt lgkmcnt(6)" : "+v"(vlo[v]), "+v"(vhi[v]), "+v"(vlo[v + 1]), "+v"(vhi[v + 1]),
+                       "+v"(vlo[v + C::DT - 1]), "+v"(vhi[v + C::DT - 1]));
+      } else {
+        if (kc == 3)
+          asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vlo[v]), "+v"(vhi[v]), "+v"(vlo[v + 1]), "+v"(vhi[v + 1]));
+        else
+          asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(vlo[v]), "+v"(vhi[v]), "+v"(vlo[v + 1]), "+v"(vhi[v + 1]));
+      }
+#pragma unroll
+      for (int d = 0; d < C::DT; ++d) {
+        typedef short shortx8 __attribute__((ext_vector_type(8)));
+        shortx8 both = __builtin_shufflevector(vlo[v + d], vhi[v + d], 0, 1, 2, 3, 4, 5, 6, 7);
+        if (C::ONES && d == DH / 32 && l32 == DH % 32) {   // the row of ones: sum of the probabilities
+#pragma unroll
+          for (int e = 0; e < 8; ++e) both[e] = (short)0x3F80;
+        }
+        vf[v + d] = __builtin_bit_cast(bf16x8, both);
+      }
+    };
     bf16x8 pf[4];
     float psum = 0.f;
     int slot = NEXT ? 4 : 0;
 #pragma unroll
     for (int g = 0; g < 16; ++g) {
-      if (g % 3 == 0 && g / 3 < 4) {
-        const int kc = g / 3;
-#pragma unroll
-        for (int d = 0; d < C::DT; ++d) {
-          const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s4_ptr_t)(sv + tr_off[d][0] + kc * 16 * C::KROW));
-          const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s4_ptr_t)(sv + tr_off[d][1] + kc * 16 * C::KROW));
-          typedef short shortx8 __attribute__((ext_vector_type(8)));
-          shortx8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          if (C::ONES && d == DH / 32 && l32 == DH % 32) {   // the row of ones: sum of the probabilities
-#pragma unroll
-            for (int e = 0; e < 8; ++e) both[e] = (short)0x3F80;
-          }
-          vf[kc * C::DT + d] = __builtin_bit_cast(bf16x8, both);
-        }
-      }
+      if (g % 3 == 0 && g / 3 < 4) vt_issue(g / 3);
 #pragma unroll
       for (int e = 2 * g; e < 2 * g + 2; ++e) {
-        const bf16_t pb = (bf16_t)__builtin_amdgcn_exp2f(s_cur[e >> 4][e & 15] * p.scale_log2 - mb);
+        const bf16_t pb = (bf16_t)__builtin_amdgcn_exp2f(s_cur[e >> 4][e & 15] * p.scale_log2);
         pf[e >> 3][e & 7] = pb;
         if (!C::ONES) psum += (float)pb;
       }
@@ -321,6 +402,7 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
       } else if (slot < M) {
         const int v = slot - NQ, kc = v / C::DT, d = v - kc * C::DT;
         if (g >= 4 * kc + 3) {
+          if (d == 0) vt_ready(kc);
           oacc[d] = mfma32(vf[v], pf[kc], oacc[d]);
           ++slot;
         }
@@ -334,6 +416,7 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
           FA_SLOT_QK(sl);
         } else {
           const int v = sl - NQ, kc = v / C::DT, d = v - kc * C::DT;
+          if (d == 0) vt_ready(kc);
           oacc[d] = mfma32(vf[v], pf[kc], oacc[d]);
         }
       }
@@ -363,7 +446,7 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
     const int cur_ = it & 1;                                                                            \
     if (it + 2 < n_tiles) FA_LOAD(0, (it + 2) * KT, cur_, it + 2);                                      \
     FENCE();                                                                                            \
-    tile_step(BoolTag<HAS_NEXT>{}, cur_, S_CUR, S_NXT);                                                 \
+    tile_step(BoolTag<HAS_NEXT>{}, it == 0, cur_, S_CUR, S_NXT);                                                 \
     FENCE();                                                                                            \
     if (HAS_NEXT) {                                                                                     \
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K of tile it+2 (and V of tile it+1) has landed */ \
@@ -432,14 +515,14 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
           *reinterpret_cast<bf16x4 *>(orow + d0) = ov;
         }
       }
-    if (p.lse && lh == 0) p.lse[tok * p.H + h] = m_run * p.scale + __logf(l_tot);
+    if (p.lse && lh == 0) p.lse[tok * p.H + h] = m_ref * p.scale + __logf(l_tot);
   }
 }
 
 template <int DH>
 int launch_dh(const FlashParams &p, int n_groups, hipStream_t s) {
   using C = Cfg<DH>;
-  constexpr int smem = 2 * C::STAGE + C::OVERRUN;
+  constexpr int smem = 2 * C::STAGE;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_flash_attn<DH>),
@@ -474,6 +557,7 @@ int launch_flash_attn(const AttnArgs &a, hipStream_t s) {
   for (int i = 0; i < 64; ++i) p.kv_len[i] = a.kv_len[i];
   p.scale = 1.0f / sqrtf((float)a.dh);
   p.scale_log2 = p.scale * 1.4426950408889634f;
+  p.rebase = 8.0f / p.scale_log2;
   if ((int64_t)a.n_groups * a.H > 0x3fffffff) {
     set_error("attention grid too large (groups=%d heads=%d)", a.n_groups, a.H);
     return -2;
