@@ -317,7 +317,8 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
       const float mq = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = (first || mq > p.rebase) ? (float)(bf16_t)(m_ref + mq) : m_ref;
       const float delta = m_new - m_ref;
-      const float alpha = __builtin_amdgcn_exp2f(-delta * p.scale_log2);
+      // (the first tile moves the reference from 0, possibly far down: O and the sum are still zero)
+      const float alpha = first ? 1.0f : __builtin_amdgcn_exp2f(-delta * p.scale_log2);
 #pragma unroll
       for (int d = 0; d < C::DT; ++d)
 #pragma unroll

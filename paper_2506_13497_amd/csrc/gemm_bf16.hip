@@ -255,6 +255,36 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TN][TM], unsigned 
     static_assert(PR * CPR % NT == 0 && ITERS % 2 == 0, "row pieces must divide evenly over the threads, in pairs");
     const int64_t sample1_tok = (my_sample0 + 1) * p.tokens_per_sample;   // first token of the tile's second sample
     float *const x_tile = p.resid + my_row0 * (int64_t)p.n + my_col0;
+    // The reads of x run DEPTH groups (of G row pieces per thread) ahead of their use, across the
+    // passes: memory requests complete in order, loads and stores alike, so a group's loads are
+    // issued BEFORE the stores of the groups processed while they are in flight, and waiting for
+    // them never waits for a store.  The piece indices start from an opaque copy of the thread
+    // index: otherwise the compiler hoists every address out of the tile loop and keeps them in
+    // registers across the k loop.
+    constexpr int G = ITERS % 4 == 0 ? 4 : 2;
+    constexpr int GP = ITERS / G;            // groups per pass
+    constexpr int NG = TM * GP;              // groups per tile
+    constexpr int DEPTH = NG < 3 ? NG : 3;
+    int tq = tid;
+    asm volatile("" : "+v"(tq));
+    float4 xr[DEPTH][G];
+    auto issue_x = [&](int g, int slot) {
+      const int b = g / GP, u0 = (g - b * GP) * G;
+      int tg = tq;
+      asm volatile("" : "+v"(tg));   // per group: nothing of its index arithmetic is shared or kept
+#pragma unroll
+      for (int j = 0; j < G; ++j) {
+        const int idx = tg + NT * (u0 + j);
+        const int rl = idx / CPR, c = idx - rl * CPR;
+        const int trow = (rl >> 5) * (TM * 32) + b * 32 + (rl & 31);   // row inside the tile
+        const bool ok = my_row0 + trow < p.N && my_col0 + c * 4 < p.n;
+        xr[slot][j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ok) xr[slot][j] = *reinterpret_cast<const float4 *>(x_tile + (trow * p.n + c * 4));
+      }
+    };
+#pragma unroll
+    for (int g = 0; g < DEPTH; ++g) issue_x(g, g);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
       {
@@ -294,33 +324,22 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TN][TM], unsigned 
           }
       }
       lds_barrier();
-      // update of x on whole-row pieces, a few at a time (this epilogue is not the fast path: the
-      // denoising step adds its branches in the streaming kernels instead)
-      constexpr int G = ITERS % 4 == 0 ? 4 : 2;
-#pragma unroll 1
-      for (int u0 = 0; u0 < ITERS; u0 += G) {
-        float4 xr[G];
-        int off[G];      // element offset from the tile's first element, or -1
-        uintx4 piece[G];
+      // update of x on whole-row pieces
 #pragma unroll
-        for (int j = 0; j < G; ++j) {
-          const int idx = tid + NT * (u0 + j);
-          const int rl = idx / CPR, c = idx - rl * CPR;
-          const int trow = (rl >> 5) * (TM * 32) + b * 32 + (rl & 31);   // row inside the tile
-          const bool ok = my_row0 + trow < p.N && my_col0 + c * 4 < p.n;
-          off[j] = ok ? trow * p.n + c * 4 : -1;
-          xr[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-          if (ok) xr[j] = *reinterpret_cast<const float4 *>(x_tile + off[j]);
-        }
+      for (int i = 0; i < GP; ++i) {
+        const int g = b * GP + i, slot = g % DEPTH, u0 = i * G;
+        uintx4 piece[G];
+        int tg = tq;
+        asm volatile("" : "+v"(tg));
 #pragma unroll
         for (int j = 0; j < G; j += 2) {
           uintx4 two[2];
           unsigned la[2];
 #pragma unroll
-          for (int e = 0; e < 2; ++e) {
-            const int idx = tid + NT * (u0 + j + e);
+          for (int e2 = 0; e2 < 2; ++e2) {
+            const int idx = tg + NT * (u0 + j + e2);
             const int rl = idx / CPR, c = idx - rl * CPR;
-            la[e] = stage_base + rl * C::PITCH_F32 + c * 16;
+            la[e2] = stage_base + rl * C::PITCH_F32 + c * 16;
           }
           lds_read2_b128(two, la[0], la[1]);
           piece[j] = two[0];
@@ -328,19 +347,24 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TN][TM], unsigned 
         }
 #pragma unroll
         for (int j = 0; j < G; ++j) {
-          if (off[j] >= 0) {
-            float4 r = xr[j];
+          const int idx = tg + NT * (u0 + j);
+          const int rl = idx / CPR, c = idx - rl * CPR;
+          const int trow = (rl >> 5) * (TM * 32) + b * 32 + (rl & 31);   // row inside the tile
+          if (my_row0 + trow < p.N && my_col0 + c * 4 < p.n) {
+            float4 r = xr[slot][j];
             r.x += __uint_as_float(piece[j][0]); r.y += __uint_as_float(piece[j][1]);
             r.z += __uint_as_float(piece[j][2]); r.w += __uint_as_float(piece[j][3]);
-            *reinterpret_cast<float4 *>(x_tile + off[j]) = r;
+            *reinterpret_cast<float4 *>(x_tile + (trow * p.n + c * 4)) = r;
             if (p.out) {
-              const int trow = off[j] / p.n;
               bf16x4 o;
               o[0] = (bf16_t)r.x; o[1] = (bf16_t)r.y; o[2] = (bf16_t)r.z; o[3] = (bf16_t)r.w;
-              *reinterpret_cast<bf16x4 *>(p.out + (my_row0 + trow) * p.ld_out + my_col0 + (off[j] - trow * p.n)) = o;
+              *reinterpret_cast<bf16x4 *>(p.out + (my_row0 + trow) * p.ld_out + my_col0 + c * 4) = o;
             }
           }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if (g + DEPTH < NG) issue_x(g + DEPTH, slot);
+        __builtin_amdgcn_sched_barrier(0);
       }
       lds_barrier();   // the staging area is rewritten by the next pass / the next tile's loads
     }
