@@ -49,7 +49,11 @@
 
 namespace {
 
-constexpr int QT = 128;   // queries per workgroup
+#ifndef FA_NW
+#define FA_NW 4
+#endif
+constexpr int NW = FA_NW;      // wavefronts per workgroup
+constexpr int QT = 32 * NW;    // queries per workgroup
 constexpr int KT = 64;    // keys per LDS tile
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
@@ -113,11 +117,22 @@ template <bool V>
 struct BoolTag { static constexpr bool value = V; };
 
 template <int DH>
-__global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
+__global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
   using C = Cfg<DH>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lh = lane >> 5;
+  // The scalar arguments of the set-up are fetched in ONE batch: left to itself the compiler
+  // fetches each where it is first used, one memory latency after the other.
+  {
+    const int a0 = p.spread, a1 = p.n_qtiles, a2 = p.n_units, a3 = p.H, a4 = p.g_inner, a5 = p.use_kv_len,
+              a6 = p.Lk_max, a7 = p.Lq;
+    const int64_t b0 = p.q_outer, b1 = p.q_inner, b2 = p.kv_outer, b3 = p.kv_inner, b4 = p.q_tok_step,
+                  b5 = p.kv_tok_step, b6 = p.ld_q, b7 = p.ld_kv;
+    const void *c0 = p.q, *c1 = p.k, *c2 = p.v;
+    asm volatile("" ::"s"(a0), "s"(a1), "s"(a2), "s"(a3), "s"(a4), "s"(a5), "s"(a6), "s"(a7), "s"(b0), "s"(b1),
+                 "s"(b2), "s"(b3), "s"(b4), "s"(b5), "s"(b6), "s"(b7), "s"(c0), "s"(c1), "s"(c2));
+  }
   // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  All query tiles of a
   // (group, head) unit read the same K/V, so a unit lives on ONE XCD: unit u on XCD u % 8, its
   // query tiles consecutive there.
@@ -179,11 +194,11 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
 
   // ---- K and V tiles, global -> LDS: wave-wide load j fills LDS bytes [1024 j, 1024 j + 1024) of a
   // tile; this lane's piece is LDS chunk m = 64 j + lane = (key m / DCH, chunk slot m % DCH)
-  constexpr int TJ = (C::T_INSTR + 3) / 4;   // loads per wave and tile (the last one only on some waves)
+  constexpr int TJ = (C::T_INSTR + NW - 1) / NW;   // loads per wave and tile (the last one only on some waves)
   int t_key[TJ], t_col[TJ];
 #pragma unroll
   for (int i = 0; i < TJ; ++i) {
-    const int m = 64 * (wave + 4 * i) + lane;
+    const int m = 64 * (wave + NW * i) + lane;
     const int key = m / C::DCH, slot = m - key * C::DCH;
     t_key[i] = key;
     t_col[i] = (C::SWZ ? (slot ^ (key & 7)) : slot) * 8;
@@ -202,17 +217,17 @@ __global__ __launch_bounds__(256, 2) void k_flash_attn(FlashParams p) {
     if ((KEY0) + KT <= Lk) {                                                                            \
       const int64_t toff_ = (int64_t)(TILE_IDX) * KT * kv_row;                                          \
       _Pragma("unroll") for (int i = 0; i < TJ; ++i) {                                                  \
-        if (wave + 4 * i < C::T_INSTR)                                                                  \
+        if (wave + NW * i < C::T_INSTR)                                                                 \
           __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_ + t_off[i] + toff_),                        \
-                                           (lds_ptr_t)(dst_ + (wave + 4 * i) * 1024), 16, 0, 0);        \
+                                           (lds_ptr_t)(dst_ + (wave + NW * i) * 1024), 16, 0, 0);       \
       }                                                                                                 \
     } else {                                                                                            \
       _Pragma("unroll") for (int i = 0; i < TJ; ++i) {                                                  \
-        if (wave + 4 * i < C::T_INSTR) {                                                                \
+        if (wave + NW * i < C::T_INSTR) {                                                               \
           int key_ = (KEY0) + t_key[i];                                                                 \
           if (key_ > Lk - 1) key_ = Lk - 1; /* tail keys re-read the last valid key; masked below */    \
           __builtin_amdgcn_global_load_lds((gbl_ptr_t)(src_ + key_ * kv_row + t_col[i]),                \
-                                           (lds_ptr_t)(dst_ + (wave + 4 * i) * 1024), 16, 0, 0);        \
+                                           (lds_ptr_t)(dst_ + (wave + NW * i) * 1024), 16, 0, 0);       \
         }                                                                                               \
       }                                                                                                 \
     }                                                                                                   \
@@ -533,7 +548,7 @@ int launch_dh(const FlashParams &p, int n_groups, hipStream_t s) {
   }
   const int64_t blocks = (p.spread ? (int64_t)p.n_units : (int64_t)((p.n_units + 7) / 8) * 8) * p.n_qtiles;
   if (blocks > 0x7fffffff) { ddit::set_error("attention: too many workgroups"); return -2; }
-  hipLaunchKernelGGL(k_flash_attn<DH>, dim3((unsigned)blocks), dim3(256), smem, s, p);
+  hipLaunchKernelGGL(k_flash_attn<DH>, dim3((unsigned)blocks), dim3(64 * NW), smem, s, p);
   return ddit::hip_fail(hipGetLastError(), "flash attention launch");
 }
 
