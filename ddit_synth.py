@@ -199,5 +199,44 @@ def make_attn_inputs(kind: str, sh: Shape, base: int, q_scale: float = 1.0,
             "v": normal_bits((base + 100, 9200, 2), ks, 1.0)}
 
 
+# ---- latent-in / latent-out layers and the sampling loop -------------------------------------
+_IO_TENSORS = ["w_patch", "b_patch", "w_y1", "b_y1", "w_y2", "b_y2", "final_table", "w_final", "b_final"]
+
+
+def io_shapes(sh: Shape, C: int, C_text: int, C_out: int) -> Dict[str, tuple]:
+    D = sh.D
+    return {"w_patch": (D, 4 * C), "b_patch": (D,), "w_y1": (D, C_text), "b_y1": (D,),
+            "w_y2": (D, D), "b_y2": (D,), "final_table": (2, D), "w_final": (4 * C_out, D),
+            "b_final": (4 * C_out,)}
+
+
+def make_io_weights(sh: Shape, base: int, C: int, C_text: int, C_out: int, w_std: float = 0.02,
+                    patch_std: float = 0.25, final_std: float = 0.05) -> Dict[str, np.ndarray]:
+    """Weights of the patch embedder, the caption embedder and the output head: bf16 bit patterns;
+    ``final_table`` as fp32 holding bf16-representable values."""
+    out = {}
+    shapes = io_shapes(sh, C, C_text, C_out)
+    for tid, name in enumerate(_IO_TENSORS):
+        key = (base, 9300, tid)
+        std = patch_std if name == "w_patch" else final_std if name == "w_final" else w_std
+        if name == "final_table":
+            out[name] = bits_to_f32(normal_bits(key, shapes[name], 0.5))
+        else:
+            out[name] = normal_bits(key, shapes[name], std)
+    return out
+
+
+def make_latent(sh: Shape, base: int, C: int) -> np.ndarray:
+    """Latent video z [B,C,T,2Hp,2Wp] ~ N(0,1) (the start of the reverse process), fp32 holding
+    bf16-representable values."""
+    return bits_to_f32(normal_bits((base, 9400, 0), (sh.B, C, sh.T, 2 * sh.Hp, 2 * sh.Wp), 1.0))
+
+
+def make_caption(sh: Shape, base: int, C_text: int, which: int = 0) -> np.ndarray:
+    """Text-encoder output c [B,Ly,C_text] ~ N(0,1) as bf16 bit patterns (which = 1: a second,
+    'unconditional' input)."""
+    return normal_bits((base, 9400, 1 + which), (sh.B, sh.Ly, C_text), 1.0)
+
+
 def small_variant(sh: Shape, **kw) -> Shape:
     return replace(sh, **kw)
