@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-#define DDIT_ABI_VERSION 1u
+#define DDIT_ABI_VERSION 2u
 
 typedef enum {
   DDIT_OK = 0,
@@ -185,6 +185,72 @@ int ddit_linear_fwd(int epilogue, const void *u, int64_t ld_u, const void *W, co
 int ddit_timestep_conditioning(const ddit_shape *shape, const ddit_step_weights *weights,
                                const float *timesteps_host, const float *temb_or_null, float *c6_out,
                                float *scratch, void *hip_stream);
+
+/* ---- latent in, latent out, and the sampling loop of eq. 1 -------------------------------
+ *
+ * Section 2.1 states the reverse process: from Gaussian noise x_T, each step calls the model on
+ * (x_t, t, c) and a solver Phi turns its prediction into x_{t-1}; section 2.2 places the DiT
+ * between the text encoder and the VAE, working on a latent video.  The paper gives neither the
+ * embedding of the latent into tokens, nor the output head, nor Phi; the forms below are this
+ * library's reading of the public spatial-temporal DiT design:
+ *   latent z fp32 [B, C, T, 2Hp, 2Wp]; token (b,t,i,j), s = i*Wp + j, is the 1x2x2 patch
+ *   z[b, :, t, 2i:2i+2, 2j:2j+2] flattened as (c, di, dj), embedded by Linear(4C -> D), plus a
+ *   fixed 2-D sine/cosine position code (quarters of D: sin(j w_m), cos(j w_m), sin(i w_m),
+ *   cos(i w_m), w_m = 10000^(-m/(D/4)));
+ *   text c bf16 [B, Ly, C_text] -> y = W_y2 GELU_tanh(W_y1 c + b_y1) + b_y2;
+ *   head: LN(x) (1 + scale_b) + shift_b with (shift_b, scale_b) = final_table[2,D] + temb_b,
+ *   then Linear(D -> 4 C_out) ordered (di, dj, c), scattered back to [B, C_out, T, 2Hp, 2Wp];
+ *   Phi: z += (t_next - t) / 1000 * eps, eps = eps_u + guidance (eps_c - eps_u) when an
+ *   unconditional text input is given, else eps_c; a run of n steps visits t_i = 1000 (1 - i/n).
+ * Latents and predictions are fp32 (a latent is a few MB); D must be a multiple of 8 and of 4,
+ * 4 C_in <= 64, 4 C_out <= 64, C_text a multiple of 8. */
+typedef struct {
+  uint32_t struct_size;          /* sizeof(ddit_io_weights) */
+  int32_t C_in, C_out, C_text;
+  const void *w_patch, *b_patch; /* bf16 [D, 4 C_in], [D]   */
+  const void *w_y1, *b_y1;       /* bf16 [D, C_text], [D]   */
+  const void *w_y2, *b_y2;       /* bf16 [D, D], [D]        */
+  const float *final_table;      /* fp32 [2, D]: shift, scale */
+  const void *w_final, *b_final; /* bf16 [4 C_out, D], [4 C_out] */
+} ddit_io_weights;
+
+/* Bytes of workspace for ddit_embed_latent / ddit_embed_caption / ddit_eps_theta / ddit_sample
+ * (it contains ddit_workspace_bytes(shape)). */
+int ddit_io_workspace_bytes(const ddit_shape *shape, const ddit_io_weights *io, size_t *bytes_out);
+
+/* x_out bf16 [B,T,S,D] = patch embedding of z + position code. */
+int ddit_embed_latent(const ddit_shape *shape, const ddit_io_weights *io, const float *z, void *x_out,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* y_out bf16 [B,Ly,D] from the text encoder's output c_text bf16 [B,Ly,C_text]. */
+int ddit_embed_caption(const ddit_shape *shape, const ddit_io_weights *io, const void *c_text, void *y_out,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* eps_out fp32 [B,C_out,T,2Hp,2Wp] from tokens x bf16 [B,T,S,D] and temb (device fp32 [B,D]). */
+int ddit_output_head(const ddit_shape *shape, const ddit_io_weights *io, const void *x, const float *temb,
+                     float *eps_out, void *hip_stream);
+
+/* The whole model on a latent: embed z, run ddit_denoise_step at timesteps_host (HOST fp32 [B])
+ * with the embedded text y bf16 [B,Ly,D] (valid lengths HOST int32[B] or NULL), apply the head. */
+int ddit_eps_theta(const ddit_shape *shape, const ddit_step_weights *weights, const ddit_io_weights *io,
+                   const float *z, const void *y, const int32_t *y_valid_len_host, const float *timesteps_host,
+                   float *eps_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* z[b] += (t_next_host[b] - t_host[b]) / 1000 * (eps_u + guidance (eps_c - eps_u)); eps_u may be
+ * NULL (then eps = eps_c).  z, eps_* fp32 with `per_sample` elements per sample, B samples. */
+int ddit_solver_step(float *z, const float *eps_c, const float *eps_u_or_null, float guidance,
+                     const float *t_host, const float *t_next_host, int32_t B, int64_t per_sample,
+                     void *hip_stream);
+
+/* Steps first_step .. last_step-1 of an n_steps run, in place on z.  A caller that schedules at
+ * step granularity (the paper's sections 4.2-4.3 change a request's resources between steps)
+ * calls this with one step, or a few, at a time; nothing is kept between calls but z.
+ * y_uncond_or_null bf16 [B,Ly,D]: unconditional text input for guidance (its valid length is Ly).
+ * eps_scratch: device fp32, 2 * B * C_out * T * 2Hp * 2Wp floats. */
+int ddit_sample(const ddit_shape *shape, const ddit_step_weights *weights, const ddit_io_weights *io, float *z,
+                const void *y, const int32_t *y_valid_len_host, const void *y_uncond_or_null, float guidance,
+                int32_t n_steps, int32_t first_step, int32_t last_step, float *eps_scratch, void *workspace,
+                size_t workspace_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

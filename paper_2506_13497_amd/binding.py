@@ -25,7 +25,8 @@ _TAP_DTYPE = {"x_after_attn": torch.float32, "x_after_cross": torch.float32, "x_
 
 EXPORTS = ["ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_workspace_bytes", "ddit_tap_region",
            "ddit_attn_fwd", "ddit_stdit_block_fwd", "ddit_denoise_step", "ddit_modulated_layernorm_fwd",
-           "ddit_linear_fwd", "ddit_timestep_conditioning"]
+           "ddit_linear_fwd", "ddit_timestep_conditioning", "ddit_io_workspace_bytes", "ddit_embed_latent",
+           "ddit_embed_caption", "ddit_output_head", "ddit_eps_theta", "ddit_solver_step", "ddit_sample"]
 
 
 class ddit_shape(C.Structure):
@@ -50,6 +51,14 @@ class ddit_block_weights(C.Structure):
 class ddit_step_weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("w_t1", "b_t1", "w_t2", "b_t2", "w_ada", "b_ada")] + \
                [("blocks", C.POINTER(ddit_block_weights))]
+
+
+_IO_FIELDS = ["w_patch", "b_patch", "w_y1", "b_y1", "w_y2", "b_y2", "final_table", "w_final", "b_final"]
+
+
+class ddit_io_weights(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("C_in", C.c_int32), ("C_out", C.c_int32), ("C_text", C.c_int32)] + \
+               [(n, C.c_void_p) for n in _IO_FIELDS]
 
 
 class DditError(RuntimeError):
@@ -85,6 +94,16 @@ def _load() -> C.CDLL:
                                     C.c_int64, C.c_void_p]
     lib.ddit_timestep_conditioning.argtypes = [C.POINTER(ddit_shape), C.POINTER(ddit_step_weights),
                                                C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    SP, WP, IP, VP, FP = C.POINTER(ddit_shape), C.POINTER(ddit_step_weights), C.POINTER(ddit_io_weights), C.c_void_p, \
+        C.POINTER(C.c_float)
+    lib.ddit_io_workspace_bytes.argtypes = [SP, IP, C.POINTER(C.c_size_t)]
+    lib.ddit_embed_latent.argtypes = [SP, IP, VP, VP, VP, C.c_size_t, VP]
+    lib.ddit_embed_caption.argtypes = [SP, IP, VP, VP, VP, C.c_size_t, VP]
+    lib.ddit_output_head.argtypes = [SP, IP, VP, VP, VP, VP]
+    lib.ddit_eps_theta.argtypes = [SP, WP, IP, VP, VP, C.POINTER(C.c_int32), FP, VP, VP, C.c_size_t, VP]
+    lib.ddit_solver_step.argtypes = [VP, VP, VP, C.c_float, FP, FP, C.c_int32, C.c_int64, VP]
+    lib.ddit_sample.argtypes = [SP, WP, IP, VP, VP, C.POINTER(C.c_int32), VP, C.c_float, C.c_int32, C.c_int32,
+                                C.c_int32, VP, VP, C.c_size_t, VP]
     for n in EXPORTS:
         if n not in ("ddit_abi_version", "ddit_status_string", "ddit_last_error"):
             getattr(lib, n).restype = C.c_int
@@ -205,6 +224,62 @@ def ddit_timestep_conditioning(shape: ddit_shape, weights: ddit_step_weights, ti
     ts = None if timesteps is None else (C.c_float * len(timesteps))(*[float(t) for t in timesteps])
     _check(_lib.ddit_timestep_conditioning(C.byref(shape), C.byref(weights), ts, _ptr(temb), _ptr(c6_out),
                                            _ptr(scratch), _stream()))
+
+
+def io_struct(w: Dict[str, torch.Tensor], C_in: int, C_out: int, C_text: int) -> ddit_io_weights:
+    s = ddit_io_weights()
+    s.struct_size = C.sizeof(ddit_io_weights)
+    s.C_in, s.C_out, s.C_text = C_in, C_out, C_text
+    for n in _IO_FIELDS:
+        t = w.get(n)
+        setattr(s, n, None if t is None else t.data_ptr())
+    return s
+
+
+def _floats(vals):
+    return None if vals is None else (C.c_float * len(vals))(*[float(v) for v in vals])
+
+
+def _nbytes(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def ddit_io_workspace_bytes(shape: ddit_shape, io: ddit_io_weights) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.ddit_io_workspace_bytes(C.byref(shape), C.byref(io), C.byref(n)))
+    return int(n.value)
+
+
+def ddit_embed_latent(shape: ddit_shape, io: ddit_io_weights, z, x_out, workspace) -> None:
+    _check(_lib.ddit_embed_latent(C.byref(shape), C.byref(io), _ptr(z), _ptr(x_out), _ptr(workspace),
+                                  _nbytes(workspace), _stream()))
+
+
+def ddit_embed_caption(shape: ddit_shape, io: ddit_io_weights, c_text, y_out, workspace) -> None:
+    _check(_lib.ddit_embed_caption(C.byref(shape), C.byref(io), _ptr(c_text), _ptr(y_out), _ptr(workspace),
+                                   _nbytes(workspace), _stream()))
+
+
+def ddit_output_head(shape: ddit_shape, io: ddit_io_weights, x, temb, eps_out) -> None:
+    _check(_lib.ddit_output_head(C.byref(shape), C.byref(io), _ptr(x), _ptr(temb), _ptr(eps_out), _stream()))
+
+
+def ddit_eps_theta(shape: ddit_shape, weights: ddit_step_weights, io: ddit_io_weights, z, y, y_valid_len, timesteps,
+                   eps_out, workspace) -> None:
+    _check(_lib.ddit_eps_theta(C.byref(shape), C.byref(weights), C.byref(io), _ptr(z), _ptr(y), _i32(y_valid_len),
+                               _floats(timesteps), _ptr(eps_out), _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def ddit_solver_step(z, eps_c, eps_u, guidance: float, t, t_next, per_sample: int) -> None:
+    _check(_lib.ddit_solver_step(_ptr(z), _ptr(eps_c), _ptr(eps_u), guidance, _floats(t), _floats(t_next), len(t),
+                                 per_sample, _stream()))
+
+
+def ddit_sample(shape: ddit_shape, weights: ddit_step_weights, io: ddit_io_weights, z, y, y_valid_len, y_uncond,
+                guidance: float, n_steps: int, first_step: int, last_step: int, eps_scratch, workspace) -> None:
+    _check(_lib.ddit_sample(C.byref(shape), C.byref(weights), C.byref(io), _ptr(z), _ptr(y), _i32(y_valid_len),
+                            _ptr(y_uncond), guidance, n_steps, first_step, last_step, _ptr(eps_scratch),
+                            _ptr(workspace), _nbytes(workspace), _stream()))
 
 
 # ----------------------------------------------------------------------------- helpers (no arithmetic)

@@ -79,4 +79,13 @@ struct CondArgs {
 int launch_timestep_conditioning(const CondArgs &c, const void *w_t1, const void *b_t1, const void *w_t2,
                                  const void *b_t2, const void *w_ada, const void *b_ada, const float *temb_in,
                                  float *c6_out, float *scratch, hipStream_t s);
+
+// layers around the token-space step, solver
+int launch_position_code(float *pos, int Hp, int Wp, int D, hipStream_t s);
+int launch_patch_embed(const float *z, const void *W, const void *bias, const float *pos, void *x, int B, int C,
+                       int T, int Hp, int Wp, int D, hipStream_t s);
+int launch_output_head(const void *x, const float *temb, const float *table, const void *W, const void *bias,
+                       float *out, int B, int C_out, int T, int Hp, int Wp, int D, float eps, hipStream_t s);
+int launch_solver_step(float *z, const float *ec, const float *eu, float guidance, const float *dt, int B,
+                       int64_t per_sample, hipStream_t s);
 }  // namespace ddit

@@ -239,6 +239,54 @@ int check_common(const Dims &d, const Layout &lo, const void *x_in, const void *
   return DDIT_OK;
 }
 
+// ---- latent in / latent out ----------------------------------------------------------------
+struct IoLayout {
+  size_t step;      // the step's own workspace starts at 0
+  size_t pos, x_tok, x_res, cap, cond, total;
+};
+
+int check_io(const ddit_shape *sh, const Dims &d, const ddit_io_weights *io) {
+  if (!io) { set_error("io weights are NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (io->struct_size != sizeof(ddit_io_weights)) {
+    set_error("io->struct_size=%u, this library expects %zu", io->struct_size, sizeof(ddit_io_weights));
+    return DDIT_ERR_INVALID_ARG;
+  }
+  if (io->C_in < 1 || io->C_out < 1 || io->C_text < 1) {
+    set_error("io: C_in=%d C_out=%d C_text=%d must be positive", io->C_in, io->C_out, io->C_text);
+    return DDIT_ERR_INVALID_ARG;
+  }
+  if (4 * io->C_in > 64 || 4 * io->C_out > 64) {
+    set_error("io: C_in=%d, C_out=%d: at most 16 latent channels", io->C_in, io->C_out); return DDIT_ERR_UNSUPPORTED;
+  }
+  if (io->C_text % 8) { set_error("io: C_text=%d must be a multiple of 8", io->C_text); return DDIT_ERR_UNSUPPORTED; }
+  if (d.D % 4) { set_error("D=%lld must be a multiple of 4 for the position code", (long long)d.D); return DDIT_ERR_UNSUPPORTED; }
+  (void)sh;
+  return DDIT_OK;
+}
+
+void make_io_layout(const Dims &d, uint32_t flags, IoLayout *lo) {
+  Layout st;
+  make_layout(d, flags, &st);
+  size_t off = st.total;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  lo->step = 0;
+  lo->pos = take((size_t)d.S * d.D * 4);
+  lo->x_tok = take((size_t)d.N * d.D * 2);
+  lo->x_res = take((size_t)d.N * d.D * 2);
+  lo->cap = take((size_t)d.B * d.Ly * d.D * 2);
+  lo->cond = take((size_t)d.B * (256 + 2 * d.D) * 4 + (size_t)d.B * 6 * d.D * 4);
+  lo->total = off;
+}
+
+int check_ws(void *ws, size_t ws_bytes, size_t need) {
+  if (!ws || ws_bytes < need) {
+    set_error("workspace of %zu bytes given, %zu required", ws ? ws_bytes : (size_t)0, need);
+    return DDIT_ERR_WORKSPACE;
+  }
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) { set_error("workspace must be 256-byte aligned"); return DDIT_ERR_ALIGNMENT; }
+  return DDIT_OK;
+}
+
 }  // namespace
 }  // namespace ddit
 
@@ -441,6 +489,134 @@ int ddit_linear_fwd(int epilogue, const void *u, int64_t ld_u, const void *W, co
   }
   g.out = out; g.ld_out = ld_out;
   return launch_gemm(epilogue, g, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+int ddit_io_workspace_bytes(const ddit_shape *shape, const ddit_io_weights *io, size_t *bytes_out) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  DDIT_TRY(check_io(shape, d, io));
+  if (!bytes_out) { set_error("bytes_out is NULL"); return DDIT_ERR_INVALID_ARG; }
+  IoLayout lo;
+  make_io_layout(d, shape->flags, &lo);
+  *bytes_out = lo.total;
+  return DDIT_OK;
+}
+
+int ddit_embed_latent(const ddit_shape *shape, const ddit_io_weights *io, const float *z, void *x_out,
+                      void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  DDIT_TRY(check_io(shape, d, io));
+  if (!z || !x_out || !io->w_patch) { set_error("z, x_out and w_patch must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (!aligned16(z) || !aligned16(x_out) || !aligned16(io->w_patch)) {
+    set_error("z, x_out and w_patch must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT;
+  }
+  IoLayout lo;
+  make_io_layout(d, shape->flags, &lo);
+  DDIT_TRY(check_ws(workspace, workspace_bytes, lo.total));
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  float *pos = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(workspace) + lo.pos);
+  DDIT_TRY(launch_position_code(pos, shape->Hp, shape->Wp, shape->D, s));
+  return launch_patch_embed(z, io->w_patch, io->b_patch, pos, x_out, shape->B, io->C_in, shape->T, shape->Hp,
+                            shape->Wp, shape->D, s);
+}
+
+int ddit_embed_caption(const ddit_shape *shape, const ddit_io_weights *io, const void *c_text, void *y_out,
+                       void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  DDIT_TRY(check_io(shape, d, io));
+  if (!c_text || !y_out || !io->w_y1 || !io->w_y2) { set_error("c_text, y_out, w_y1 and w_y2 must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (!aligned16(c_text) || !aligned16(y_out) || !aligned16(io->w_y1) || !aligned16(io->w_y2) ||
+      (io->b_y1 && !aligned16(io->b_y1)) || (io->b_y2 && !aligned16(io->b_y2))) {
+    set_error("caption embedder: pointers must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT;
+  }
+  IoLayout lo;
+  make_io_layout(d, shape->flags, &lo);
+  DDIT_TRY(check_ws(workspace, workspace_bytes, lo.total));
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  void *tmp = reinterpret_cast<unsigned char *>(workspace) + lo.cap;
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.u = c_text; g.ld_u = io->C_text; g.W = io->w_y1; g.bias = io->b_y1; g.N = d.B * d.Ly; g.n = (int)d.D;
+  g.k = io->C_text; g.out = tmp; g.ld_out = d.D; g.tokens_per_sample = d.Ly;
+  DDIT_TRY(launch_gemm(DDIT_EPI_GELU_BF16, g, s));
+  g.u = tmp; g.ld_u = d.D; g.W = io->w_y2; g.bias = io->b_y2; g.k = (int)d.D; g.out = y_out;
+  return launch_gemm(DDIT_EPI_BF16, g, s);
+}
+
+int ddit_output_head(const ddit_shape *shape, const ddit_io_weights *io, const void *x, const float *temb,
+                     float *eps_out, void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  DDIT_TRY(check_io(shape, d, io));
+  if (!x || !temb || !eps_out || !io->final_table || !io->w_final) {
+    set_error("x, temb, eps_out, final_table and w_final must not be NULL"); return DDIT_ERR_INVALID_ARG;
+  }
+  if (!aligned16(x) || !aligned16(io->w_final)) { set_error("x and w_final must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT; }
+  return launch_output_head(x, temb, io->final_table, io->w_final, io->b_final, eps_out, shape->B, io->C_out, shape->T,
+                            shape->Hp, shape->Wp, shape->D, shape->ln_eps, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+int ddit_eps_theta(const ddit_shape *shape, const ddit_step_weights *weights, const ddit_io_weights *io,
+                   const float *z, const void *y, const int32_t *y_valid_len_host, const float *timesteps_host,
+                   float *eps_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  DDIT_TRY(check_io(shape, d, io));
+  if (!weights || !timesteps_host || !eps_out) { set_error("weights, timesteps_host and eps_out must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  IoLayout lo;
+  make_io_layout(d, shape->flags, &lo);
+  DDIT_TRY(check_ws(workspace, workspace_bytes, lo.total));
+  unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
+  void *x_tok = ws + lo.x_tok, *x_res = ws + lo.x_res;
+  float *cond = reinterpret_cast<float *>(ws + lo.cond);
+  float *c6_tmp = cond + d.B * (256 + 2 * d.D);
+  const float *temb = cond + d.B * 256 + d.B * d.D;   // where the conditioning stage leaves the timestep embedding
+  DDIT_TRY(ddit_embed_latent(shape, io, z, x_tok, workspace, workspace_bytes, hip_stream));
+  DDIT_TRY(ddit_timestep_conditioning(shape, weights, timesteps_host, nullptr, c6_tmp, cond, hip_stream));
+  DDIT_TRY(ddit_denoise_step(shape, weights, x_tok, y, y_valid_len_host, nullptr, temb, x_res, workspace,
+                             workspace_bytes, hip_stream));
+  return ddit_output_head(shape, io, x_res, temb, eps_out, hip_stream);
+}
+
+int ddit_solver_step(float *z, const float *eps_c, const float *eps_u_or_null, float guidance,
+                     const float *t_host, const float *t_next_host, int32_t B, int64_t per_sample,
+                     void *hip_stream) {
+  if (!z || !eps_c || !t_host || !t_next_host) { set_error("z, eps_c, t_host and t_next_host must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (B < 1 || B > 64 || per_sample < 0) { set_error("solver step: B=%d per_sample=%lld", B, (long long)per_sample); return DDIT_ERR_INVALID_ARG; }
+  float dt[64];
+  for (int b = 0; b < B; ++b) dt[b] = (t_next_host[b] - t_host[b]) / 1000.0f;
+  return launch_solver_step(z, eps_c, eps_u_or_null, guidance, dt, B, per_sample, reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+int ddit_sample(const ddit_shape *shape, const ddit_step_weights *weights, const ddit_io_weights *io, float *z,
+                const void *y, const int32_t *y_valid_len_host, const void *y_uncond_or_null, float guidance,
+                int32_t n_steps, int32_t first_step, int32_t last_step, float *eps_scratch, void *workspace,
+                size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  DDIT_TRY(check_io(shape, d, io));
+  if (n_steps < 1 || first_step < 0 || last_step < first_step || last_step > n_steps) {
+    set_error("sample: n_steps=%d first_step=%d last_step=%d", n_steps, first_step, last_step);
+    return DDIT_ERR_INVALID_ARG;
+  }
+  if (!z || !eps_scratch) { set_error("z and eps_scratch must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  const int64_t per_sample = (int64_t)io->C_out * d.T * 4 * d.S;
+  if (io->C_out != io->C_in) { set_error("sample: the prediction must have the latent's channels (C_out=%d, C_in=%d)", io->C_out, io->C_in); return DDIT_ERR_UNSUPPORTED; }
+  float *eps_c = eps_scratch, *eps_u = eps_scratch + d.B * per_sample;
+  for (int i = first_step; i < last_step; ++i) {
+    float t[64], tn[64];
+    for (int b = 0; b < d.B; ++b) {
+      t[b] = 1000.0f * (1.0f - (float)i / (float)n_steps);
+      tn[b] = 1000.0f * (1.0f - (float)(i + 1) / (float)n_steps);
+    }
+    DDIT_TRY(ddit_eps_theta(shape, weights, io, z, y, y_valid_len_host, t, eps_c, workspace, workspace_bytes, hip_stream));
+    if (y_uncond_or_null)
+      DDIT_TRY(ddit_eps_theta(shape, weights, io, z, y_uncond_or_null, nullptr, t, eps_u, workspace, workspace_bytes, hip_stream));
+    DDIT_TRY(ddit_solver_step(z, eps_c, y_uncond_or_null ? eps_u : nullptr, guidance, t, tn, (int)d.B, per_sample, hip_stream));
+  }
+  return DDIT_OK;
 }
 
 }  // extern "C"
