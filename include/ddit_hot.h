@@ -158,6 +158,21 @@ int ddit_denoise_step(const ddit_shape *shape, const ddit_step_weights *weights,
                       const float *temb_or_null, void *x_out, void *workspace, size_t workspace_bytes,
                       void *hip_stream);
 
+/* The text condition is constant over a request's steps (section 2.1: every step is called with
+ * the same c), so the cross-attention keys and values of every layer, k|v = y W_ckv^T + b_ckv,
+ * can be formed once per request instead of once per step.
+ * ddit_cross_kv_bytes: size of that cache, bf16 [2*n_blocks, B*Ly, 2A] in layer order (block 0
+ * spatial, block 0 temporal, block 1 spatial, ...).  ddit_cross_kv_precompute fills it.
+ * ddit_denoise_step_cached is ddit_denoise_step reading the cache instead of projecting y
+ * (y is then unused and may be NULL; cross_kv NULL = project y as usual). */
+int ddit_cross_kv_bytes(const ddit_shape *shape, size_t *bytes_out);
+int ddit_cross_kv_precompute(const ddit_shape *shape, const ddit_step_weights *weights, const void *y,
+                             void *cross_kv_out, void *hip_stream);
+int ddit_denoise_step_cached(const ddit_shape *shape, const ddit_step_weights *weights, const void *x_in,
+                             const void *y, const void *cross_kv_or_null, const int32_t *y_valid_len_host,
+                             const float *timesteps_host, const float *temb_or_null, void *x_out,
+                             void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* ---- single stages of the path, exported for kernel-level parity tests and profiling ---- */
 
 /* out[n,:] = bf16( LN(x[n,:]) * (1 + scale_b) + shift_b ), LN without affine over D with
@@ -231,10 +246,12 @@ int ddit_output_head(const ddit_shape *shape, const ddit_io_weights *io, const v
                      float *eps_out, void *hip_stream);
 
 /* The whole model on a latent: embed z, run ddit_denoise_step at timesteps_host (HOST fp32 [B])
- * with the embedded text y bf16 [B,Ly,D] (valid lengths HOST int32[B] or NULL), apply the head. */
+ * with the embedded text y bf16 [B,Ly,D] (valid lengths HOST int32[B] or NULL), apply the head.
+ * cross_kv_or_null: a cache from ddit_cross_kv_precompute for this y (then y may be NULL). */
 int ddit_eps_theta(const ddit_shape *shape, const ddit_step_weights *weights, const ddit_io_weights *io,
-                   const float *z, const void *y, const int32_t *y_valid_len_host, const float *timesteps_host,
-                   float *eps_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+                   const float *z, const void *y, const void *cross_kv_or_null, const int32_t *y_valid_len_host,
+                   const float *timesteps_host, float *eps_out, void *workspace, size_t workspace_bytes,
+                   void *hip_stream);
 
 /* z[b] += (t_next_host[b] - t_host[b]) / 1000 * (eps_u + guidance (eps_c - eps_u)); eps_u may be
  * NULL (then eps = eps_c).  z, eps_* fp32 with `per_sample` elements per sample, B samples. */
@@ -246,9 +263,12 @@ int ddit_solver_step(float *z, const float *eps_c, const float *eps_u_or_null, f
  * step granularity (the paper's sections 4.2-4.3 change a request's resources between steps)
  * calls this with one step, or a few, at a time; nothing is kept between calls but z.
  * y_uncond_or_null bf16 [B,Ly,D]: unconditional text input for guidance (its valid length is Ly).
+ * cross_kv_or_null / cross_kv_uncond_or_null: caches from ddit_cross_kv_precompute for y and
+ * y_uncond (kept by the caller across calls); with guidance either both or none are given.
  * eps_scratch: device fp32, 2 * B * C_out * T * 2Hp * 2Wp floats. */
 int ddit_sample(const ddit_shape *shape, const ddit_step_weights *weights, const ddit_io_weights *io, float *z,
-                const void *y, const int32_t *y_valid_len_host, const void *y_uncond_or_null, float guidance,
+                const void *y, const int32_t *y_valid_len_host, const void *y_uncond_or_null,
+                const void *cross_kv_or_null, const void *cross_kv_uncond_or_null, float guidance,
                 int32_t n_steps, int32_t first_step, int32_t last_step, float *eps_scratch, void *workspace,
                 size_t workspace_bytes, void *hip_stream);
 

@@ -26,7 +26,8 @@ _TAP_DTYPE = {"x_after_attn": torch.float32, "x_after_cross": torch.float32, "x_
 EXPORTS = ["ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_workspace_bytes", "ddit_tap_region",
            "ddit_attn_fwd", "ddit_stdit_block_fwd", "ddit_denoise_step", "ddit_modulated_layernorm_fwd",
            "ddit_linear_fwd", "ddit_timestep_conditioning", "ddit_io_workspace_bytes", "ddit_embed_latent",
-           "ddit_embed_caption", "ddit_output_head", "ddit_eps_theta", "ddit_solver_step", "ddit_sample"]
+           "ddit_embed_caption", "ddit_output_head", "ddit_eps_theta", "ddit_solver_step", "ddit_sample",
+           "ddit_cross_kv_bytes", "ddit_cross_kv_precompute", "ddit_denoise_step_cached"]
 
 
 class ddit_shape(C.Structure):
@@ -100,9 +101,12 @@ def _load() -> C.CDLL:
     lib.ddit_embed_latent.argtypes = [SP, IP, VP, VP, VP, C.c_size_t, VP]
     lib.ddit_embed_caption.argtypes = [SP, IP, VP, VP, VP, C.c_size_t, VP]
     lib.ddit_output_head.argtypes = [SP, IP, VP, VP, VP, VP]
-    lib.ddit_eps_theta.argtypes = [SP, WP, IP, VP, VP, C.POINTER(C.c_int32), FP, VP, VP, C.c_size_t, VP]
+    lib.ddit_eps_theta.argtypes = [SP, WP, IP, VP, VP, VP, C.POINTER(C.c_int32), FP, VP, VP, C.c_size_t, VP]
+    lib.ddit_cross_kv_bytes.argtypes = [SP, C.POINTER(C.c_size_t)]
+    lib.ddit_cross_kv_precompute.argtypes = [SP, WP, VP, VP, VP]
+    lib.ddit_denoise_step_cached.argtypes = [SP, WP, VP, VP, VP, C.POINTER(C.c_int32), FP, VP, VP, VP, C.c_size_t, VP]
     lib.ddit_solver_step.argtypes = [VP, VP, VP, C.c_float, FP, FP, C.c_int32, C.c_int64, VP]
-    lib.ddit_sample.argtypes = [SP, WP, IP, VP, VP, C.POINTER(C.c_int32), VP, C.c_float, C.c_int32, C.c_int32,
+    lib.ddit_sample.argtypes = [SP, WP, IP, VP, VP, C.POINTER(C.c_int32), VP, VP, VP, C.c_float, C.c_int32, C.c_int32,
                                 C.c_int32, VP, VP, C.c_size_t, VP]
     for n in EXPORTS:
         if n not in ("ddit_abi_version", "ddit_status_string", "ddit_last_error"):
@@ -265,9 +269,27 @@ def ddit_output_head(shape: ddit_shape, io: ddit_io_weights, x, temb, eps_out) -
 
 
 def ddit_eps_theta(shape: ddit_shape, weights: ddit_step_weights, io: ddit_io_weights, z, y, y_valid_len, timesteps,
-                   eps_out, workspace) -> None:
-    _check(_lib.ddit_eps_theta(C.byref(shape), C.byref(weights), C.byref(io), _ptr(z), _ptr(y), _i32(y_valid_len),
-                               _floats(timesteps), _ptr(eps_out), _ptr(workspace), _nbytes(workspace), _stream()))
+                   eps_out, workspace, cross_kv=None) -> None:
+    _check(_lib.ddit_eps_theta(C.byref(shape), C.byref(weights), C.byref(io), _ptr(z), _ptr(y), _ptr(cross_kv),
+                               _i32(y_valid_len), _floats(timesteps), _ptr(eps_out), _ptr(workspace),
+                               _nbytes(workspace), _stream()))
+
+
+def ddit_cross_kv_bytes(shape: ddit_shape) -> int:
+    n = C.c_size_t(0)
+    _check(_lib.ddit_cross_kv_bytes(C.byref(shape), C.byref(n)))
+    return int(n.value)
+
+
+def ddit_cross_kv_precompute(shape: ddit_shape, weights: ddit_step_weights, y, cross_kv_out) -> None:
+    _check(_lib.ddit_cross_kv_precompute(C.byref(shape), C.byref(weights), _ptr(y), _ptr(cross_kv_out), _stream()))
+
+
+def ddit_denoise_step_cached(shape: ddit_shape, weights: ddit_step_weights, x_in, y, cross_kv, y_valid_len, timesteps,
+                             temb, x_out, workspace) -> None:
+    _check(_lib.ddit_denoise_step_cached(C.byref(shape), C.byref(weights), _ptr(x_in), _ptr(y), _ptr(cross_kv),
+                                         _i32(y_valid_len), _floats(timesteps), _ptr(temb), _ptr(x_out),
+                                         _ptr(workspace), _nbytes(workspace), _stream()))
 
 
 def ddit_solver_step(z, eps_c, eps_u, guidance: float, t, t_next, per_sample: int) -> None:
@@ -276,10 +298,11 @@ def ddit_solver_step(z, eps_c, eps_u, guidance: float, t, t_next, per_sample: in
 
 
 def ddit_sample(shape: ddit_shape, weights: ddit_step_weights, io: ddit_io_weights, z, y, y_valid_len, y_uncond,
-                guidance: float, n_steps: int, first_step: int, last_step: int, eps_scratch, workspace) -> None:
+                guidance: float, n_steps: int, first_step: int, last_step: int, eps_scratch, workspace,
+                cross_kv=None, cross_kv_uncond=None) -> None:
     _check(_lib.ddit_sample(C.byref(shape), C.byref(weights), C.byref(io), _ptr(z), _ptr(y), _i32(y_valid_len),
-                            _ptr(y_uncond), guidance, n_steps, first_step, last_step, _ptr(eps_scratch),
-                            _ptr(workspace), _nbytes(workspace), _stream()))
+                            _ptr(y_uncond), _ptr(cross_kv), _ptr(cross_kv_uncond), guidance, n_steps, first_step,
+                            last_step, _ptr(eps_scratch), _ptr(workspace), _nbytes(workspace), _stream()))
 
 
 # ----------------------------------------------------------------------------- helpers (no arithmetic)

@@ -164,13 +164,15 @@ struct Taps {
 #define DDIT_TRY(expr) do { int rc_ = (expr); if (rc_ != DDIT_OK) return rc_; } while (0)
 
 // One layer on the fp32 stream x (in the workspace).
-int run_layer(ddit_attn_kind kind, const Dims &d, const ddit_layer_weights &w, const void *y, const int32_t *valid_len,
-              const float *c6, float eps, unsigned char *ws, const Layout &lo, const Taps &tp, hipStream_t s) {
+// kvc_cached: this layer's cross-attention k|v [B*Ly, 2A] formed earlier, or null (then y is projected here)
+int run_layer(ddit_attn_kind kind, const Dims &d, const ddit_layer_weights &w, const void *y, const void *kvc_cached,
+              const int32_t *valid_len, const float *c6, float eps, unsigned char *ws, const Layout &lo,
+              const Taps &tp, hipStream_t s) {
   float *x = reinterpret_cast<float *>(ws + lo.x);
   void *xh = ws + lo.xh;
   unsigned char *qkv = ws + lo.qkv;
   void *o = ws + lo.o;
-  unsigned char *kvc = ws + lo.kvc;
+  const unsigned char *kvc = kvc_cached ? reinterpret_cast<const unsigned char *>(kvc_cached) : ws + lo.kvc;
   void *h = ws + lo.h;
   const int64_t N = d.N, D = d.D, A = d.A, M = d.M;
 
@@ -199,8 +201,10 @@ int run_layer(ddit_attn_kind kind, const Dims &d, const ddit_layer_weights &w, c
   // cross-attention branch (reads the stream itself; ungated)
   base(xh, D, w.w_cq, w.b_cq, N, (int)A, (int)D); g.out = qkv; g.ld_out = 3 * A;
   DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
-  base(y, D, w.w_ckv, w.b_ckv, d.B * d.Ly, (int)(2 * A), (int)D); g.out = kvc; g.ld_out = 2 * A;
-  DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
+  if (!kvc_cached) {
+    base(y, D, w.w_ckv, w.b_ckv, d.B * d.Ly, (int)(2 * A), (int)D); g.out = ws + lo.kvc; g.ld_out = 2 * A;
+    DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
+  }
   if (tp.on) {  // q_c lives strided inside the qkv buffer: copy it out row by row
     DDIT_TRY(hip_fail(hipMemcpy2DAsync(tp.ws + lo.tap_off[tp.layer][DDIT_TAP_QC], A * 2, qkv, 3 * A * 2, A * 2, N,
                                        hipMemcpyDeviceToDevice, s), "tap copy"));
@@ -377,9 +381,9 @@ int ddit_stdit_block_fwd(const ddit_shape *shape, const ddit_block_weights *weig
   float *x = reinterpret_cast<float *>(ws + lo.x);
   Taps tp{(shape->flags & DDIT_FLAG_TAPS) != 0, ws, &lo, 0, s};
   DDIT_TRY(launch_cast_bf16_to_f32(x_in, x, d.N * d.D, s));
-  DDIT_TRY(run_layer(DDIT_ATTN_SPATIAL, d, weights->spatial, y, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+  DDIT_TRY(run_layer(DDIT_ATTN_SPATIAL, d, weights->spatial, y, nullptr, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
   tp.layer = 1;
-  DDIT_TRY(run_layer(DDIT_ATTN_TEMPORAL, d, weights->temporal, y, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+  DDIT_TRY(run_layer(DDIT_ATTN_TEMPORAL, d, weights->temporal, y, nullptr, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
   return launch_cast_f32_to_bf16(x, x_out, d.N * d.D, s);
 }
 
@@ -407,15 +411,64 @@ int ddit_timestep_conditioning(const ddit_shape *shape, const ddit_step_weights 
                                       reinterpret_cast<hipStream_t>(hip_stream));
 }
 
+int ddit_cross_kv_bytes(const ddit_shape *shape, size_t *bytes_out) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  if (!bytes_out) { set_error("bytes_out is NULL"); return DDIT_ERR_INVALID_ARG; }
+  *bytes_out = (size_t)2 * shape->n_blocks * d.B * d.Ly * 2 * d.A * 2;
+  return DDIT_OK;
+}
+
+int ddit_cross_kv_precompute(const ddit_shape *shape, const ddit_step_weights *weights, const void *y,
+                             void *cross_kv_out, void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  if (!weights || !y || !cross_kv_out) { set_error("weights, y and cross_kv_out must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (shape->n_blocks > 0 && !weights->blocks) { set_error("weights->blocks is NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (!aligned16(y) || !aligned16(cross_kv_out)) { set_error("y and cross_kv_out must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT; }
+  for (int i = 0; i < shape->n_blocks; ++i)
+    for (const ddit_layer_weights *w : {&weights->blocks[i].spatial, &weights->blocks[i].temporal}) {
+      if (!w->w_ckv) { set_error("block %d: w_ckv is NULL", i); return DDIT_ERR_INVALID_ARG; }
+      if (!aligned16(w->w_ckv) || (w->b_ckv && !aligned16(w->b_ckv))) { set_error("block %d: w_ckv/b_ckv not 16-byte aligned", i); return DDIT_ERR_ALIGNMENT; }
+    }
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  const size_t per_layer = (size_t)d.B * d.Ly * 2 * d.A * 2;
+  unsigned char *out = reinterpret_cast<unsigned char *>(cross_kv_out);
+  for (int i = 0; i < shape->n_blocks; ++i) {
+    int l = 0;
+    for (const ddit_layer_weights *w : {&weights->blocks[i].spatial, &weights->blocks[i].temporal}) {
+      GemmArgs g;
+      memset(&g, 0, sizeof(g));
+      g.u = y; g.ld_u = d.D; g.W = w->w_ckv; g.bias = w->b_ckv; g.N = d.B * d.Ly; g.n = (int)(2 * d.A); g.k = (int)d.D;
+      g.out = out + (size_t)(2 * i + l) * per_layer; g.ld_out = 2 * d.A; g.tokens_per_sample = d.Ly;
+      DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
+      ++l;
+    }
+  }
+  return DDIT_OK;
+}
+
 int ddit_denoise_step(const ddit_shape *shape, const ddit_step_weights *weights, const void *x_in,
                       const void *y, const int32_t *y_valid_len_host, const float *timesteps_host,
                       const float *temb_or_null, void *x_out, void *workspace, size_t workspace_bytes,
                       void *hip_stream) {
+  return ddit_denoise_step_cached(shape, weights, x_in, y, nullptr, y_valid_len_host, timesteps_host, temb_or_null,
+                                  x_out, workspace, workspace_bytes, hip_stream);
+}
+
+int ddit_denoise_step_cached(const ddit_shape *shape, const ddit_step_weights *weights, const void *x_in,
+                             const void *y, const void *cross_kv_or_null, const int32_t *y_valid_len_host,
+                             const float *timesteps_host, const float *temb_or_null, void *x_out,
+                             void *workspace, size_t workspace_bytes, void *hip_stream) {
   Dims d;
   DDIT_TRY(check_shape(shape, &d));
   Layout lo;
   make_layout(d, shape->flags, &lo);
   if (!weights) { set_error("weights is NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (cross_kv_or_null) {
+    if (!aligned16(cross_kv_or_null)) { set_error("cross_kv must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT; }
+    if (!y) y = cross_kv_or_null;   // y is not read when every layer's k|v is cached; keep the checks below uniform
+  }
   if (shape->n_blocks > 0 && !weights->blocks) { set_error("weights->blocks is NULL"); return DDIT_ERR_INVALID_ARG; }
   DDIT_TRY(check_common(d, lo, x_in, y, x_out, workspace, workspace_bytes));
   DDIT_TRY(check_valid_len(y_valid_len_host, d));
@@ -431,11 +484,15 @@ int ddit_denoise_step(const ddit_shape *shape, const ddit_step_weights *weights,
                                       reinterpret_cast<float *>(ws + lo.cond), hip_stream));
   Taps tp{(shape->flags & DDIT_FLAG_TAPS) != 0, ws, &lo, 0, s};
   DDIT_TRY(launch_cast_bf16_to_f32(x_in, x, d.N * d.D, s));
+  const size_t kv_layer = (size_t)d.B * d.Ly * 2 * d.A * 2;
+  const unsigned char *kv = reinterpret_cast<const unsigned char *>(cross_kv_or_null);
   for (int i = 0; i < shape->n_blocks; ++i) {
     tp.layer = 0;
-    DDIT_TRY(run_layer(DDIT_ATTN_SPATIAL, d, weights->blocks[i].spatial, y, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+    DDIT_TRY(run_layer(DDIT_ATTN_SPATIAL, d, weights->blocks[i].spatial, y, kv ? kv + (size_t)(2 * i) * kv_layer : nullptr,
+                       y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
     tp.layer = 1;
-    DDIT_TRY(run_layer(DDIT_ATTN_TEMPORAL, d, weights->blocks[i].temporal, y, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+    DDIT_TRY(run_layer(DDIT_ATTN_TEMPORAL, d, weights->blocks[i].temporal, y,
+                       kv ? kv + (size_t)(2 * i + 1) * kv_layer : nullptr, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
   }
   return launch_cast_f32_to_bf16(x, x_out, d.N * d.D, s);
 }
@@ -559,8 +616,9 @@ int ddit_output_head(const ddit_shape *shape, const ddit_io_weights *io, const v
 }
 
 int ddit_eps_theta(const ddit_shape *shape, const ddit_step_weights *weights, const ddit_io_weights *io,
-                   const float *z, const void *y, const int32_t *y_valid_len_host, const float *timesteps_host,
-                   float *eps_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+                   const float *z, const void *y, const void *cross_kv_or_null, const int32_t *y_valid_len_host,
+                   const float *timesteps_host, float *eps_out, void *workspace, size_t workspace_bytes,
+                   void *hip_stream) {
   Dims d;
   DDIT_TRY(check_shape(shape, &d));
   DDIT_TRY(check_io(shape, d, io));
@@ -575,8 +633,8 @@ int ddit_eps_theta(const ddit_shape *shape, const ddit_step_weights *weights, co
   const float *temb = cond + d.B * 256 + d.B * d.D;   // where the conditioning stage leaves the timestep embedding
   DDIT_TRY(ddit_embed_latent(shape, io, z, x_tok, workspace, workspace_bytes, hip_stream));
   DDIT_TRY(ddit_timestep_conditioning(shape, weights, timesteps_host, nullptr, c6_tmp, cond, hip_stream));
-  DDIT_TRY(ddit_denoise_step(shape, weights, x_tok, y, y_valid_len_host, nullptr, temb, x_res, workspace,
-                             workspace_bytes, hip_stream));
+  DDIT_TRY(ddit_denoise_step_cached(shape, weights, x_tok, y, cross_kv_or_null, y_valid_len_host, nullptr, temb, x_res,
+                                    workspace, workspace_bytes, hip_stream));
   return ddit_output_head(shape, io, x_res, temb, eps_out, hip_stream);
 }
 
@@ -591,7 +649,8 @@ int ddit_solver_step(float *z, const float *eps_c, const float *eps_u_or_null, f
 }
 
 int ddit_sample(const ddit_shape *shape, const ddit_step_weights *weights, const ddit_io_weights *io, float *z,
-                const void *y, const int32_t *y_valid_len_host, const void *y_uncond_or_null, float guidance,
+                const void *y, const int32_t *y_valid_len_host, const void *y_uncond_or_null,
+                const void *cross_kv_or_null, const void *cross_kv_uncond_or_null, float guidance,
                 int32_t n_steps, int32_t first_step, int32_t last_step, float *eps_scratch, void *workspace,
                 size_t workspace_bytes, void *hip_stream) {
   Dims d;
@@ -602,6 +661,9 @@ int ddit_sample(const ddit_shape *shape, const ddit_step_weights *weights, const
     return DDIT_ERR_INVALID_ARG;
   }
   if (!z || !eps_scratch) { set_error("z and eps_scratch must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (y_uncond_or_null && ((cross_kv_or_null != nullptr) != (cross_kv_uncond_or_null != nullptr))) {
+    set_error("sample: with guidance give both cross-attention caches or none"); return DDIT_ERR_INVALID_ARG;
+  }
   const int64_t per_sample = (int64_t)io->C_out * d.T * 4 * d.S;
   if (io->C_out != io->C_in) { set_error("sample: the prediction must have the latent's channels (C_out=%d, C_in=%d)", io->C_out, io->C_in); return DDIT_ERR_UNSUPPORTED; }
   float *eps_c = eps_scratch, *eps_u = eps_scratch + d.B * per_sample;
@@ -611,9 +673,11 @@ int ddit_sample(const ddit_shape *shape, const ddit_step_weights *weights, const
       t[b] = 1000.0f * (1.0f - (float)i / (float)n_steps);
       tn[b] = 1000.0f * (1.0f - (float)(i + 1) / (float)n_steps);
     }
-    DDIT_TRY(ddit_eps_theta(shape, weights, io, z, y, y_valid_len_host, t, eps_c, workspace, workspace_bytes, hip_stream));
+    DDIT_TRY(ddit_eps_theta(shape, weights, io, z, y, cross_kv_or_null, y_valid_len_host, t, eps_c, workspace,
+                            workspace_bytes, hip_stream));
     if (y_uncond_or_null)
-      DDIT_TRY(ddit_eps_theta(shape, weights, io, z, y_uncond_or_null, nullptr, t, eps_u, workspace, workspace_bytes, hip_stream));
+      DDIT_TRY(ddit_eps_theta(shape, weights, io, z, y_uncond_or_null, cross_kv_uncond_or_null, nullptr, t, eps_u,
+                              workspace, workspace_bytes, hip_stream));
     DDIT_TRY(ddit_solver_step(z, eps_c, y_uncond_or_null ? eps_u : nullptr, guidance, t, tn, (int)d.B, per_sample, hip_stream));
   }
   return DDIT_OK;

@@ -214,3 +214,48 @@ def test_io_argument_errors(lib):
         lib.ddit_sample(st.shape, st.step, st.io, z, y, None, None, 1.0, 4, 3, 5, scratch, st.ws)
     assert e.value.status == lib.DDIT_ERR_INVALID_ARG
     assert torch.equal(z, to_dev(st.z)), "nothing may run on an argument error"
+
+
+def test_cross_attention_cache(lib):
+    """The per-request cache of cross-attention keys/values: its contents against the oracle's
+    projection, and a step (and a guided sampling run) reading it against the same call projecting
+    the text itself: bit-identical, the kernels and their inputs being the same."""
+    sh = syn.small_variant(IO_CASES[0][0], n_blocks=2)
+    st = Setup(lib, sh, IO_CASES[0][1], IO_CASES[0][2])
+    y, y_u = st.caption_dev(lib, st.c_text), st.caption_dev(lib, st.c_unc)
+    nbytes = lib.ddit_cross_kv_bytes(st.shape)
+    assert nbytes == 2 * sh.n_blocks * sh.B * sh.Ly * 2 * sh.A * 2
+    kv = torch.full((nbytes // 2,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    kv_u = torch.empty_like(kv)
+    lib.ddit_cross_kv_precompute(st.shape, st.step, y, kv)
+    lib.ddit_cross_kv_precompute(st.shape, st.step, y_u, kv_u)
+    torch.cuda.synchronize()
+    got = dev_to_f64(kv).reshape(2 * sh.n_blocks, sh.B, sh.Ly, 2 * sh.A)
+    yf = dev_to_f64(y)
+    for layer, (blk, kind) in enumerate([(0, "spatial"), (0, "temporal"), (1, "spatial"), (1, "temporal")]):
+        w = st.f_blocks[blk][kind]
+        assert_parity(got[layer], ora.linear(yf, w["w_ckv"], w["b_ckv"]), "cached k|v of layer %d" % layer)
+    # one token-space step
+    x = to_dev(syn.make_activations(sh, 41)["x"])
+    valid = [sh.Ly - 2, sh.Ly]
+    outs = []
+    for cache in (None, kv):
+        o = torch.full((sh.B, sh.T, sh.S, sh.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lib.ddit_denoise_step_cached(st.shape, st.step, x, None if cache is not None else y, cache, valid, [300.0, 600.0],
+                                     None, o, st.ws)
+        outs.append(o)
+    torch.cuda.synchronize()
+    assert torch.isfinite(outs[0].float()).all() and torch.equal(outs[0], outs[1])
+    # a guided sampling run
+    z0 = to_dev(st.z)
+    scratch = torch.empty(2 * z0.numel(), dtype=torch.float32, device="cuda")
+    runs = []
+    for caches in ((None, None), (kv, kv_u)):
+        z = z0.clone()
+        lib.ddit_sample(st.shape, st.step, st.io, z, y, valid, y_u, 2.5, 4, 0, 2, scratch, st.ws, caches[0], caches[1])
+        runs.append(z)
+    torch.cuda.synchronize()
+    assert torch.equal(runs[0], runs[1])
+    with pytest.raises(lib.DditError) as e:
+        lib.ddit_sample(st.shape, st.step, st.io, z0.clone(), y, valid, y_u, 2.5, 4, 0, 1, scratch, st.ws, kv, None)
+    assert e.value.status == lib.DDIT_ERR_INVALID_ARG
