@@ -156,6 +156,57 @@ def test_linear_and_layernorm_validation(m):
     assert lib.ddit_modulated_layernorm_fwd(None, P(0x2000), P(0x3000), 0, 4, 4, 64, 1e-6, P(0x4000), None) == -1
 
 
+def _io(m, **kw):
+    d = dict(C_in=4, C_out=4, C_text=64)
+    d.update(kw)
+    io = m.binding.ddit_io_weights()
+    io.struct_size = C.sizeof(m.binding.ddit_io_weights)
+    io.C_in, io.C_out, io.C_text = d["C_in"], d["C_out"], d["C_text"]
+    return io
+
+
+def test_io_workspace_and_cache_sizes(m):
+    sh = _shape(m)
+    step = m.ddit_workspace_bytes(sh)
+    total = m.ddit_io_workspace_bytes(sh, _io(m))
+    N, D, S, Ly = 256, 256, 64, 16
+    extra = S * D * 4 + 2 * N * D * 2 + Ly * D * 2
+    assert step + extra <= total <= step + extra + 64 * 1024
+    assert m.ddit_cross_kv_bytes(_shape(m, n_blocks=3)) == 2 * 3 * Ly * 2 * 256 * 2
+
+
+@pytest.mark.parametrize("kw,code", [(dict(C_in=17), -2), (dict(C_out=0), -1), (dict(C_text=60), -2)])
+def test_bad_io_weights_are_rejected(m, kw, code):
+    with pytest.raises(m.binding.DditError) as e:
+        m.ddit_io_workspace_bytes(_shape(m), _io(m, **kw))
+    assert e.value.status == code
+
+
+def test_io_struct_size_and_sample_ranges(m):
+    lib = m.binding._lib
+    sh = _shape(m)
+    io = _io(m)
+    io.struct_size = 8
+    n = C.c_size_t(0)
+    assert lib.ddit_io_workspace_bytes(C.byref(sh), C.byref(io), C.byref(n)) == -1
+    assert "struct_size" in m.ddit_last_error()
+    io = _io(m)
+    sw = m.binding.ddit_step_weights()
+    P = C.c_void_p
+    args = lambda n_steps, first, last, z=0x1000: (C.byref(sh), C.byref(sw), C.byref(io), P(z), P(0x2000), None, None, None, None,
+                                                   C.c_float(1.0), n_steps, first, last, P(0x3000), P(0x100000), 1 << 30, None)
+    assert lib.ddit_sample(*args(0, 0, 0)) == -1          # no steps
+    assert lib.ddit_sample(*args(4, 3, 2)) == -1          # range reversed
+    assert lib.ddit_sample(*args(4, 0, 5)) == -1          # past the end
+    assert lib.ddit_sample(*args(4, 0, 1, z=0)) == -1     # NULL latent
+    assert lib.ddit_sample(*args(4, 2, 2)) == 0           # an empty range does nothing
+    # solver step: B outside 1..64, NULL pointers
+    assert lib.ddit_solver_step(P(0x1000), P(0x2000), None, C.c_float(1.0), (C.c_float * 1)(1.0), (C.c_float * 1)(0.0), 0, 10, None) == -1
+    assert lib.ddit_solver_step(None, P(0x2000), None, C.c_float(1.0), (C.c_float * 1)(1.0), (C.c_float * 1)(0.0), 1, 10, None) == -1
+    # cache precompute: NULL y
+    assert lib.ddit_cross_kv_precompute(C.byref(sh), C.byref(sw), None, P(0x1000), None) == -1
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
