@@ -166,7 +166,28 @@ def main():
         ms = time_call(lambda: m.ddit_modulated_layernorm_fwd(x32, lw["ada_table"], c6, 0, sh.L, 1e-6, xh), reps)
         gbs = 6.0 * N * D / (ms * 1e-3) / 1e9
         stages["modulated_layernorm"] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
-        del xh, h, qkv, o, kvc, x32
+        # the layers around the step and the solver (latent with 4 channels, text width 4096)
+        C_lat, C_text = 4, 4096
+        io_w = {k: draw(s_, 0.02, torch.float32 if k == "final_table" else torch.bfloat16)
+                for k, s_ in syn.io_shapes(sh, C_lat, C_text, C_lat).items()}
+        io = m.io_struct(io_w, C_lat, C_lat, C_text)
+        ws_io = torch.empty(m.ddit_io_workspace_bytes(shape, io), dtype=torch.uint8, device="cuda")
+        z = torch.randn(sh.B, C_lat, sh.T, 2 * sh.Hp, 2 * sh.Wp, device="cuda")
+        eps = torch.empty_like(z)
+        temb = torch.randn(sh.B, D, device="cuda")
+        c_text = torch.randn(sh.B, sh.Ly, C_text, device="cuda").to(torch.bfloat16)
+        y_e = torch.empty(sh.B, sh.Ly, D, dtype=torch.bfloat16, device="cuda")
+        ms = time_call(lambda: m.ddit_embed_latent(shape, io, z, xh, ws_io), reps)
+        gbs = (2.0 * N * D + 4.0 * z.numel()) / (ms * 1e-3) / 1e9
+        stages["embed_latent"] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+        ms = time_call(lambda: m.ddit_output_head(shape, io, xh, temb, eps), reps)
+        gbs = (2.0 * N * D + 4.0 * z.numel()) / (ms * 1e-3) / 1e9
+        stages["output_head"] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+        ms = time_call(lambda: m.ddit_embed_caption(shape, io, c_text, y_e, ws_io), reps)
+        stages["embed_caption"] = {"ms": round(ms, 4)}
+        ms = time_call(lambda: m.ddit_solver_step(z, eps, eps, 1.0, [500.0] * sh.B, [500.0] * sh.B, z.numel() // sh.B), reps)
+        stages["solver_step"] = {"ms": round(ms, 4)}
+        del xh, h, qkv, o, kvc, x32, ws_io
         print("[bench] stages: %s" % json.dumps(stages), file=sys.stderr, flush=True)
 
     # ---- CPU oracle on a bounded sample of the same workload

@@ -8,7 +8,7 @@
 namespace {
 
 constexpr int PATCH_MAX = 64;   // 4 * channels at most
-constexpr int TOK_PER_WG = 8;
+constexpr int TOK_PER_WG = 32;
 
 // pos[s, :] for s = i*Wp + j: quarters sin(j w_m), cos(j w_m), sin(i w_m), cos(i w_m),
 // w_m = 10000^(-m/Q), Q = D/4.  Arguments stay below a few hundred radians; evaluated in fp64
@@ -28,13 +28,15 @@ __global__ void k_position_code(float *__restrict__ pos, int Hp, int Wp, int D) 
 // x[token, d] = bf16( sum_p patch[token, p] W[d, p] + bias[d] + pos[s, d] ), patch order (c, di, dj).
 // A workgroup takes TOK_PER_WG consecutive tokens: their patches go to LDS, then every thread
 // owns output features d = tid, tid + 256, ... and keeps that feature's weight row in registers
-// across the tokens.
+// across the tokens.  PC = compile-time channel count (weight rows fetched as 16-byte pieces,
+// patches read from LDS four values at a time), or 0 for any channel count.
+template <int PC>
 __global__ __launch_bounds__(256) void k_patch_embed(const float *__restrict__ z, const bf16_t *__restrict__ W,
                                                      const bf16_t *__restrict__ bias, const float *__restrict__ pos,
                                                      bf16_t *__restrict__ x, int B, int C, int T, int Hp, int Wp,
                                                      int D) {
-  __shared__ float patch[TOK_PER_WG][PATCH_MAX];
-  const int P = 4 * C;
+  __shared__ __attribute__((aligned(16))) float patch[TOK_PER_WG][PATCH_MAX];
+  const int P = PC > 0 ? 4 * PC : 4 * C;
   const int64_t S = (int64_t)Hp * Wp, N = (int64_t)B * T * S;
   const int64_t tok0 = (int64_t)blockIdx.x * TOK_PER_WG;
   for (int e = threadIdx.x; e < TOK_PER_WG * P; e += blockDim.x) {
@@ -51,21 +53,35 @@ __global__ __launch_bounds__(256) void k_patch_embed(const float *__restrict__ z
     patch[k][p] = v;
   }
   __syncthreads();
+  const int ntok = N - tok0 < TOK_PER_WG ? (int)(N - tok0) : TOK_PER_WG;
+  const int64_t s0 = tok0 % S;
   for (int d = threadIdx.x; d < D; d += blockDim.x) {
-    float w[PATCH_MAX];
+    constexpr int PW = PC > 0 ? 4 * PC : PATCH_MAX;
+    float w[PW];
+    if constexpr (PC > 0 && PC % 2 == 0) {
 #pragma unroll
-    for (int p = 0; p < PATCH_MAX; ++p) w[p] = p < P ? (float)W[(int64_t)d * P + p] : 0.f;
+      for (int p8 = 0; p8 < PW / 8; ++p8) {
+        const bf16x8 v = *reinterpret_cast<const bf16x8 *>(W + (int64_t)d * P + 8 * p8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[8 * p8 + e] = (float)v[e];
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < PW; ++p) w[p] = p < P ? (float)W[(int64_t)d * P + p] : 0.f;
+    }
     const float bd = bias ? (float)bias[d] : 0.f;
-#pragma unroll
-    for (int k = 0; k < TOK_PER_WG; ++k) {
-      const int64_t tok = tok0 + k;
-      if (tok >= N) break;
+    int64_t s = s0;
+    for (int k = 0; k < ntok; ++k) {
       float acc = 0.f;
 #pragma unroll
-      for (int p = 0; p < PATCH_MAX; ++p)
-        if (p < P) acc += patch[k][p] * w[p];
-      const int64_t s = tok % S;
-      x[tok * D + d] = (bf16_t)(acc + bd + pos[s * D + d]);
+      for (int p4 = 0; p4 < PW / 4; ++p4) {
+        if (4 * p4 < P) {
+          const float4 pv = *reinterpret_cast<const float4 *>(&patch[k][4 * p4]);
+          acc += pv.x * w[4 * p4] + pv.y * w[4 * p4 + 1] + pv.z * w[4 * p4 + 2] + pv.w * w[4 * p4 + 3];
+        }
+      }
+      x[(tok0 + k) * D + d] = (bf16_t)(acc + bd + pos[s * D + d]);
+      if (++s == S) s = 0;
     }
   }
 }
@@ -172,9 +188,14 @@ int launch_patch_embed(const float *z, const void *W, const void *bias, const fl
   const int64_t N = (int64_t)B * T * Hp * Wp;
   if (N == 0) return 0;
   if (4 * C > PATCH_MAX) { set_error("patch embedding: 4*C_in=%d exceeds %d", 4 * C, PATCH_MAX); return -2; }
-  hipLaunchKernelGGL(k_patch_embed, dim3((unsigned)((N + TOK_PER_WG - 1) / TOK_PER_WG)), dim3(256), 0, s, z,
-                     reinterpret_cast<const bf16_t *>(W), reinterpret_cast<const bf16_t *>(bias), pos,
-                     reinterpret_cast<bf16_t *>(x), B, C, T, Hp, Wp, D);
+  const dim3 grid((unsigned)((N + TOK_PER_WG - 1) / TOK_PER_WG));
+  const bf16_t *w = reinterpret_cast<const bf16_t *>(W), *bb = reinterpret_cast<const bf16_t *>(bias);
+  bf16_t *xo = reinterpret_cast<bf16_t *>(x);
+  // weight rows of 4*C bf16 are fetched as 16-byte pieces when that keeps them aligned
+  if (C == 4) hipLaunchKernelGGL(k_patch_embed<4>, grid, dim3(256), 0, s, z, w, bb, pos, xo, B, C, T, Hp, Wp, D);
+  else if (C == 8) hipLaunchKernelGGL(k_patch_embed<8>, grid, dim3(256), 0, s, z, w, bb, pos, xo, B, C, T, Hp, Wp, D);
+  else if (C == 16) hipLaunchKernelGGL(k_patch_embed<16>, grid, dim3(256), 0, s, z, w, bb, pos, xo, B, C, T, Hp, Wp, D);
+  else hipLaunchKernelGGL(k_patch_embed<0>, grid, dim3(256), 0, s, z, w, bb, pos, xo, B, C, T, Hp, Wp, D);
   return hip_fail(hipGetLastError(), "patch embedding launch");
 }
 
