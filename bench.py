@@ -54,6 +54,63 @@ def measured_traffic(workload):
     return None
 
 
+# per-step time of one rank at degree of parallelism p (section 4.2.3): latent shapes by resolution
+DOP_RESOLUTIONS = [("144p", 16, 9, 16), ("240p", 16, 15, 27), ("360p", 16, 23, 40), ("480p", 30, 30, 54),
+                   ("720p", 30, 45, 80)]
+XGMI_GBS_PER_PEER = 60.0   # assumed one-direction payload rate of one xGMI link (published 153.6 GB/s both ways)
+
+
+def dop_table(m, syn, torch, steps):
+    """DiT_step_time(parallel size p, resolution r) on this GPU for one rank of a dynamic-sequence-
+    parallel run, and the change rate z = 1 - t(p)/t(p/2) the paper's greedy scheduler derives its
+    per-resolution GPU count B from (section 4.2.3).  One rank's share: ceil(T/p) frames of the
+    request (spatial layers are sharded by frame; the temporal layers' share, S/p locations over all
+    frames, has the same token count, and every other stage is token-wise).  The two all-to-alls per
+    block are NOT run (one GPU per box): their time is modelled from the bytes and an assumed link
+    rate, and reported beside the measured compute."""
+    base_sh = syn.CONFIGS["C4"]["shape"]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    draw = lambda shape_, std, dt=torch.bfloat16: (torch.randn(shape_, generator=gen, device="cuda") * std).to(torch.bfloat16).to(dt)
+    sw = {k: draw(s_, 0.02) for k, s_ in syn.step_shapes(base_sh).items()}
+    blocks = [{kind: {n: draw(s_, 0.02, torch.float32 if n == "ada_table" else torch.bfloat16)
+                      for n, s_ in syn.layer_shapes(base_sh).items()} for kind in ("spatial", "temporal")}
+              for _ in range(base_sh.n_blocks)]
+    st = m.step_struct(sw, blocks)
+    rows = []
+    for name, T, Hp, Wp in DOP_RESOLUTIONS:
+        t_ms, comm_ms = {}, {}
+        for p in (1, 2, 4, 8):
+            Tp = -(-T // p)
+            sh = syn.small_variant(base_sh, T=Tp, Hp=Hp, Wp=Wp)
+            shape = m.make_shape(sh.B, sh.T, sh.Hp, sh.Wp, sh.D, sh.H, sh.dh, sh.M, sh.Ly, sh.n_blocks)
+            ws = m.alloc_workspace(shape)
+            x_in, y = draw((sh.B, sh.T, sh.S, sh.D), 1.0), draw((sh.B, sh.Ly, sh.D), 1.0)
+            x_out = torch.empty_like(x_in)
+            run = lambda: m.ddit_denoise_step(shape, st, x_in, y, None, [500.0], None, x_out, ws)
+            run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                run()
+            torch.cuda.synchronize()
+            t_ms[p] = (time.perf_counter() - t0) * 1e3 / steps
+            # per block two all-to-alls; a rank sends N_rank*D*2 bytes, (p-1)/p of it to p-1 peers in parallel
+            per_peer = sh.N * sh.D * 2.0 / p if p > 1 else 0.0
+            comm_ms[p] = 2 * sh.n_blocks * per_peer / (XGMI_GBS_PER_PEER * 1e9) * 1e3
+            del ws, x_in, x_out
+        z = {p: 1.0 - t_ms[p] / t_ms[p // 2] for p in (2, 4, 8)}
+        zc = {p: 1.0 - (t_ms[p] + comm_ms[p]) / (t_ms[p // 2] + comm_ms[p // 2]) for p in (2, 4, 8)}
+        rows.append({"resolution": name, "T": T, "Hp": Hp, "Wp": Wp,
+                     "step_ms": {str(p): round(v, 3) for p, v in t_ms.items()},
+                     "modelled_exchange_ms": {str(p): round(v, 3) for p, v in comm_ms.items()},
+                     "z_compute": {str(p): round(v, 4) for p, v in z.items()},
+                     "z_with_exchange": {str(p): round(v, 4) for p, v in zc.items()},
+                     "B_argmax_z_with_exchange": max(zc, key=zc.get)})
+        print("[bench] %s: %s" % (name, json.dumps(rows[-1])), file=sys.stderr, flush=True)
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +119,8 @@ def main():
     ap.add_argument("--workload", default="C4", choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-stages", action="store_true", help="skip the per-kernel timings")
+    ap.add_argument("--dop-table", action="store_true",
+                    help="instead of the benchmark line: per-rank step time by resolution and degree of parallelism")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one rank's share of the step); --gpus %d is not supported"
@@ -76,6 +135,12 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.dop_table:
+        rows = dop_table(m, syn, torch, max(args.steps // 3, 2))
+        print(json.dumps({"metric": "DiT step time (ms) of one rank by resolution and degree of parallelism", "unit": "ms",
+                          "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                          "assumed_xgmi_GBps_per_peer": XGMI_GBS_PER_PEER, "table": rows}), flush=True)
+        return
     cfg = syn.CONFIGS[args.workload]
     sh, base = cfg["shape"], cfg["base"]
 
