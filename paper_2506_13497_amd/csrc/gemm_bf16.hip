@@ -635,7 +635,9 @@ int launch_one(const GemmParams &p0, hipStream_t s) {
   using C = GemmCfg<WGM, WGN, TM, TN, NS>;
   constexpr int LDS_BYTES = C::SMEM + C::EXTRA_BYTES;
   static_assert(LDS_BYTES <= 160 * 1024, "the tile's stages must fit the LDS");
-  constexpr int WG_PER_CU = (160 * 1024) / LDS_BYTES >= 2 && C::NW <= 4 ? 2 : 1;
+  // workgroups resident per CU: what the LDS holds, at most three of the four-wavefront tiles
+  constexpr int LDS_FIT = (160 * 1024) / LDS_BYTES;
+  constexpr int WG_PER_CU = C::NW > 4 ? 1 : (LDS_FIT > 3 ? 3 : (LDS_FIT < 1 ? 1 : LDS_FIT));
   GemmParams p = p0;
   const int64_t tiles_m = (p.N + C::BM - 1) / C::BM;
   p.tiles_m = (int)tiles_m;
@@ -677,8 +679,14 @@ int launch_epi(const GemmParams &p, hipStream_t s) {
   // that more than a handful of CUs get work.
   const int64_t tiles_n = (p.n + 383) / 384;
   const int64_t big_tiles = ((p.N + 191) / 192) * tiles_n;
-  const bool big = big_tiles >= 128 && 10 * (int64_t)p.n >= 7 * 384 * tiles_n;
-  return big ? launch_one<2, 4, 3, 3, 4, EPI>(p, s) : launch_one<2, 2, 2, 2, 4, EPI>(p, s);
+  const bool big = big_tiles >= 200 && 10 * (int64_t)p.n >= 7 * 384 * tiles_n;
+  if (big) return launch_one<2, 4, 3, 3, 4, EPI>(p, s);
+  // Short token counts (a rank's share of a low-resolution request): when even the 128 x 128 tiles
+  // would leave a quarter of the chip's workgroup slots empty, 64 x 128 tiles (three workgroups per
+  // CU) put twice as many workgroups to work on the same problem, each with half the k-loop time.
+  const int64_t small_tiles = ((p.N + 127) / 128) * ((p.n + 127) / 128);
+  if (small_tiles * 4 < (int64_t)num_cus() * 2 * 3) return launch_one<2, 2, 1, 2, 4, EPI>(p, s);
+  return launch_one<2, 2, 2, 2, 4, EPI>(p, s);
 }
 
 }  // namespace
