@@ -26,8 +26,8 @@
 // of the pieces of lanes i/4, 4+i/4, 8+i/4, 12+i/4), two such reads per operand.
 // The head dim is padded to the next multiple of 16 above it for Q K^T and to 96 rows for V^T
 // (rows past the head dim read neighbouring data and produce rows of O^T that are never
-// stored); the lanes of row 72 substitute ones, so that the same MFMAs that form O also
-// accumulate the softmax denominator (of the bf16-rounded probabilities used).
+// stored); row 72 of V^T reads constant pieces holding ones, so that the same MFMAs that form O
+// also accumulate the softmax denominator (of the bf16-rounded probabilities used).
 //
 // Online softmax without per-score bookkeeping.  The first padding column of the contraction
 // (index dh) is put to work: K holds a one there (a constant 16-byte piece in LDS that the lanes
@@ -90,7 +90,12 @@ struct Cfg {
   static constexpr int T_BYTES = KT * KROW;        // one K or V tile
   static constexpr int KCONST = 2 * T_BYTES;       // offset of the constant K piece (1, 0, ..., 0) in a stage
   static constexpr int OVERRUN = 64;               // V^T rows past the head dim read up to this far past a tile
-  static constexpr int STAGE = 2 * T_BYTES + OVERRUN;   // K tile, V tile, constant piece (the rest of it is slack)
+  // After the K piece come, when the head dim leaves a spare V^T row, four 8-byte pieces (1, 0, 0, 0),
+  // 16 keys apart like the contraction chunks of the V reads: the lanes that supply the pieces of row
+  // DH of V^T point there, so the row of ones needs no substitution in registers.
+  static constexpr int VONE = KCONST + 16;
+  static constexpr int TAIL = ONES ? 3 * 16 * KROW : 0;
+  static constexpr int STAGE = 2 * T_BYTES + OVERRUN + TAIL;   // K tile, V tile, constant pieces (the rest is slack)
   static constexpr int T_INSTR = T_BYTES / 1024;   // wave-wide 16-byte direct loads per tile
   static_assert(T_BYTES % 1024 == 0, "a tile must be a whole number of wave loads");
   static_assert((DT * 32 - DH) * 2 <= OVERRUN, "overrun of the padded V^T rows");
@@ -187,9 +192,12 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
       const int row = hf * 32 + l32, c = 2 * ks + lh;
       k_off[ks][hf] = c < C::DCH ? row * C::KROW + (C::SWZ ? (c ^ (row & 7)) : c) * 16 : C::KCONST;
     }
-  if (tid < 2 * (C::OVERRUN / 4)) {   // the constant piece of both stages, and zeros in the slack after it
+  if (tid < 2 * (C::OVERRUN / 4)) {   // the constant K piece of both stages, and zeros in the slack after it
     const int st = tid / (C::OVERRUN / 4), w = tid - st * (C::OVERRUN / 4);
     *reinterpret_cast<unsigned *>(smem + st * C::STAGE + C::KCONST + 4 * w) = w == 0 ? 0x00003F80u : 0u;
+  } else if (C::ONES && tid >= 32 && tid < 32 + 2 * 4 * 2) {   // the (1, 0, 0, 0) pieces of V^T's row of ones
+    const int e = tid - 32, st = e >> 3, kc = (e >> 1) & 3, w = e & 1;
+    *reinterpret_cast<unsigned *>(smem + st * C::STAGE + C::VONE + kc * 16 * C::KROW + 4 * w) = w == 0 ? 0x00003F80u : 0u;
   }
 
   // ---- K and V tiles, global -> LDS: wave-wide load j fills LDS bytes [1024 j, 1024 j + 1024) of a
@@ -248,6 +256,8 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
       const int chunk = d >> 3;
       // past the packed row (d >= DH) the address simply runs on into the next key's row
       tr_off[dt][hf] = C::SWZ ? key * C::KROW + (((chunk ^ (key & 7)) << 4) | ((d & 7) << 1)) : key * C::KROW + d * 2;
+      // the piece that holds row DH of V^T (element 0 of d-group DH%16/4 in block DH%32/16 of tile DH/32)
+      if (C::ONES && dt == DH / 32 && tr_d == DH % 32) tr_off[dt][hf] = C::VONE - C::T_BYTES;
     }
 
   floatx16 oacc[C::DT];
@@ -391,11 +401,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
 #pragma unroll
       for (int d = 0; d < C::DT; ++d) {
         typedef short shortx8 __attribute__((ext_vector_type(8)));
-        shortx8 both = __builtin_shufflevector(vlo[v + d], vhi[v + d], 0, 1, 2, 3, 4, 5, 6, 7);
-        if (C::ONES && d == DH / 32 && l32 == DH % 32) {   // the row of ones: sum of the probabilities
-#pragma unroll
-          for (int e = 0; e < 8; ++e) both[e] = (short)0x3F80;
-        }
+        const shortx8 both = __builtin_shufflevector(vlo[v + d], vhi[v + d], 0, 1, 2, 3, 4, 5, 6, 7);
         vf[v + d] = __builtin_bit_cast(bf16x8, both);
       }
     };
