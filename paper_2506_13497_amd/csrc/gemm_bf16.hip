@@ -680,6 +680,12 @@ int launch_epi(const GemmParams &p, hipStream_t s) {
   const int64_t tiles_n = (p.n + 383) / 384;
   const int64_t big_tiles = ((p.N + 191) / 192) * tiles_n;
   const bool big = big_tiles >= 200 && 10 * (int64_t)p.n >= 7 * 384 * tiles_n;
+  // out-feature counts that are multiples of 288 but not of 384 (a head-split rank's 4 x 72 = 288
+  // attention width and its 864-wide q|k|v): a 192 x 288 tile of six wavefronts has no padding there
+  if constexpr (EPI == 0) {
+    if (p.n % 288 == 0 && p.n % 384 != 0 && ((p.N + 191) / 192) * (p.n / 288) >= 200)
+      return launch_one<2, 3, 3, 3, 4, EPI>(p, s);
+  }
   if (big) return launch_one<2, 4, 3, 3, 4, EPI>(p, s);
   // Short token counts (a rank's share of a low-resolution request): when even the 128 x 128 tiles
   // would leave a quarter of the chip's workgroup slots empty, 64 x 128 tiles (three workgroups per

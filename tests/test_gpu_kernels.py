@@ -61,10 +61,13 @@ LIN_CASES = [
     (130, 864, 1160),     # k tail (k % 32 == 8) on the small tile
     (1, 8, 8),            # a single partial k-step
     (40, 64, 72),         # two full k-steps and a tail: fewer steps than the pipeline is deep
-    # the large tile (192 x 384, eight wavefronts) needs >= 128 tiles:
-    (8200, 1152, 288),    # narrow attention width as k, ragged token tail, tiles over two samples
+    # the 192 x 288 tile (six wavefronts; out-features a multiple of 288 but not of 384) needs >= 200 tiles:
+    (13001, 864, 1160),   # q|k|v width of a 4-head share, ragged token tail, k tail
+    (40000, 288, 1152),   # one tile wide
+    # the large tile (192 x 384, eight wavefronts) needs >= 200 tiles:
+    (12900, 1152, 288),   # narrow attention width as k, ragged token tail, tiles over two samples
     (5000, 4608, 1160),   # k tail on the large tile
-    (4100, 2440, 512),    # n not a multiple of 384: ragged last out-feature tile
+    (5600, 2440, 512),    # n not a multiple of 384: ragged last out-feature tile
 ]
 
 
