@@ -119,6 +119,8 @@ def main():
     ap.add_argument("--workload", default="C4", choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-stages", action="store_true", help="skip the per-kernel timings")
+    ap.add_argument("--only-stage", default=None,
+                    help="time only this entry of 'stages' (for counter runs of one kernel), e.g. spatial_attention")
     ap.add_argument("--dop-table", action="store_true",
                     help="instead of the benchmark line: per-rank step time by resolution and degree of parallelism")
     args = ap.parse_args()
@@ -173,14 +175,17 @@ def main():
     def one_step():
         m.ddit_denoise_step(shape, st, x_in, y, valid, tsteps, None, x_out, ws)
 
+    if args.only_stage:
+        args.warmup, args.no_cpu = 0, True
+    n_steps = 0 if args.only_stage else args.steps
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(n_steps):
         one_step()
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t1) * 1e3 / max(args.steps, 1)
+    ms_per_step = max((time.perf_counter() - t1) * 1e3 / max(n_steps, 1), 1e-9)
     fl = step_flops(sh, valid)
     step_tflops = fl["step"] / (ms_per_step * 1e-3) / 1e12
     print("[bench] step %.2f ms, %.1f TFLOP/s algorithmic" % (ms_per_step, step_tflops), file=sys.stderr, flush=True)
@@ -197,23 +202,30 @@ def main():
         return e0.elapsed_time(e1) / reps   # ms
 
     stages, roofline = {}, None
+    want = lambda name: not args.only_stage or args.only_stage == name
     if not args.no_stages:
         N, D, A, M = sh.N, sh.D, sh.A, sh.M
         lw = blocks[0]["spatial"]
         xh = torch.randn(N, D, device="cuda").to(torch.bfloat16)
         h = torch.empty(N, M, dtype=torch.bfloat16, device="cuda")
         reps = max(args.steps, 5)
-        ms = time_call(lambda: m.ddit_linear_fwd(m.DDIT_EPI_GELU_BF16, xh, D, lw["w_fc1"], lw["b_fc1"], N, M, D, h, M), reps)
+        ms = time_call(lambda: m.ddit_linear_fwd(m.DDIT_EPI_GELU_BF16, xh, D, lw["w_fc1"], lw["b_fc1"], N, M, D, h, M),
+                       reps) if want("fc1_gelu") else float("nan")
         tf = fl["fc1"] / (ms * 1e-3) / 1e12
         roofline = {"kernel": "k_gemm_bf16<2,4,3,3,4,1> = 192x384 tiles, GELU epilogue (MLP fc1, %dx%dx%d)" % (N, M, D),
                     "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(tf / PEAK_BF16_TFLOPS, 4), "ms_per_launch": round(ms, 4),
                     "traffic": measured_traffic(args.workload)}
-        stages["fc1_gelu"] = {"ms": round(ms, 4), "tflops": round(tf, 1), "frac_mfma": round(tf / PEAK_BF16_TFLOPS, 4)}
+        if want("fc1_gelu"):
+            stages["fc1_gelu"] = {"ms": round(ms, 4), "tflops": round(tf, 1), "frac_mfma": round(tf / PEAK_BF16_TFLOPS, 4)}
+        else:
+            roofline = None
         qkv = torch.randn(N, 3 * A, device="cuda").to(torch.bfloat16)
         o = torch.empty(N, A, dtype=torch.bfloat16, device="cuda")
         for name, kind, flops in (("spatial_attention", m.DDIT_ATTN_SPATIAL, fl["spatial"]),
                                   ("temporal_attention", m.DDIT_ATTN_TEMPORAL, fl["temporal"])):
+            if not want(name):
+                continue
             ms = time_call(lambda: m.ddit_attn_fwd(kind, shape, qkv[:, :A], qkv[:, A:2 * A], qkv[:, 2 * A:], 3 * A, 3 * A,
                                                    None, o, A), reps)
             tf = flops / (ms * 1e-3) / 1e12
@@ -221,16 +233,18 @@ def main():
             stages[name] = {"ms": round(ms, 4), "tflops": round(tf, 1), "frac_mfma": round(tf / PEAK_BF16_TFLOPS, 4),
                             "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
         kvc = torch.randn(sh.B * sh.Ly, 2 * A, device="cuda").to(torch.bfloat16)
-        ms = time_call(lambda: m.ddit_attn_fwd(m.DDIT_ATTN_CROSS, shape, qkv[:, :A], kvc[:, :A], kvc[:, A:], 3 * A, 2 * A,
-                                               valid, o, A), reps)
-        tf = fl["cross"] / (ms * 1e-3) / 1e12
-        stages["cross_attention"] = {"ms": round(ms, 4), "tflops": round(tf, 1), "frac_mfma": round(tf / PEAK_BF16_TFLOPS, 4),
-                                     "valid_len": valid}
+        if want("cross_attention"):
+            ms = time_call(lambda: m.ddit_attn_fwd(m.DDIT_ATTN_CROSS, shape, qkv[:, :A], kvc[:, :A], kvc[:, A:], 3 * A,
+                                                   2 * A, valid, o, A), reps)
+            tf = fl["cross"] / (ms * 1e-3) / 1e12
+            stages["cross_attention"] = {"ms": round(ms, 4), "tflops": round(tf, 1),
+                                         "frac_mfma": round(tf / PEAK_BF16_TFLOPS, 4), "valid_len": valid}
         x32 = torch.randn(N, D, device="cuda")
         c6 = torch.randn(sh.B, 6 * D, device="cuda")
-        ms = time_call(lambda: m.ddit_modulated_layernorm_fwd(x32, lw["ada_table"], c6, 0, sh.L, 1e-6, xh), reps)
-        gbs = 6.0 * N * D / (ms * 1e-3) / 1e9
-        stages["modulated_layernorm"] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+        if want("modulated_layernorm"):
+            ms = time_call(lambda: m.ddit_modulated_layernorm_fwd(x32, lw["ada_table"], c6, 0, sh.L, 1e-6, xh), reps)
+            gbs = 6.0 * N * D / (ms * 1e-3) / 1e9
+            stages["modulated_layernorm"] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
         # the layers around the step and the solver (latent with 4 channels, text width 4096)
         C_lat, C_text = 4, 4096
         io_w = {k: draw(s_, 0.02, torch.float32 if k == "final_table" else torch.bfloat16)
@@ -242,16 +256,20 @@ def main():
         temb = torch.randn(sh.B, D, device="cuda")
         c_text = torch.randn(sh.B, sh.Ly, C_text, device="cuda").to(torch.bfloat16)
         y_e = torch.empty(sh.B, sh.Ly, D, dtype=torch.bfloat16, device="cuda")
-        ms = time_call(lambda: m.ddit_embed_latent(shape, io, z, xh, ws_io), reps)
-        gbs = (2.0 * N * D + 4.0 * z.numel()) / (ms * 1e-3) / 1e9
-        stages["embed_latent"] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
-        ms = time_call(lambda: m.ddit_output_head(shape, io, xh, temb, eps), reps)
-        gbs = (2.0 * N * D + 4.0 * z.numel()) / (ms * 1e-3) / 1e9
-        stages["output_head"] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
-        ms = time_call(lambda: m.ddit_embed_caption(shape, io, c_text, y_e, ws_io), reps)
-        stages["embed_caption"] = {"ms": round(ms, 4)}
-        ms = time_call(lambda: m.ddit_solver_step(z, eps, eps, 1.0, [500.0] * sh.B, [500.0] * sh.B, z.numel() // sh.B), reps)
-        stages["solver_step"] = {"ms": round(ms, 4)}
+        io_bytes = 2.0 * N * D + 4.0 * z.numel()
+        for name, fn, nbytes in (
+                ("embed_latent", lambda: m.ddit_embed_latent(shape, io, z, xh, ws_io), io_bytes),
+                ("output_head", lambda: m.ddit_output_head(shape, io, xh, temb, eps), io_bytes),
+                ("embed_caption", lambda: m.ddit_embed_caption(shape, io, c_text, y_e, ws_io), None),
+                ("solver_step", lambda: m.ddit_solver_step(z, eps, eps, 1.0, [500.0] * sh.B, [500.0] * sh.B,
+                                                           z.numel() // sh.B), None)):
+            if not want(name):
+                continue
+            ms = time_call(fn, reps)
+            stages[name] = {"ms": round(ms, 4)}
+            if nbytes:
+                gbs = nbytes / (ms * 1e-3) / 1e9
+                stages[name].update({"GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)})
         del xh, h, qkv, o, kvc, x32, ws_io
         print("[bench] stages: %s" % json.dumps(stages), file=sys.stderr, flush=True)
 
