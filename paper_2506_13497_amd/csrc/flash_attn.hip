@@ -192,11 +192,16 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
       const int row = hf * 32 + l32, c = 2 * ks + lh;
       k_off[ks][hf] = c < C::DCH ? row * C::KROW + (C::SWZ ? (c ^ (row & 7)) : c) * 16 : C::KCONST;
     }
-  if (tid < 2 * (C::OVERRUN / 4)) {   // the constant K piece of both stages, and zeros in the slack after it
+  static_assert(C::VONE == C::KCONST + 16 && C::OVERRUN >= 24, "the first piece of ones lies in the slack after the K piece");
+  if (tid < 2 * (C::OVERRUN / 4)) {
+    // per stage, the 64 bytes after the V tile: the constant K piece (1, 0, ..., 0), the first
+    // (1, 0, 0, 0) piece of V^T's row of ones, zeros in the rest (padded V^T rows read it); every
+    // word has exactly one writer
     const int st = tid / (C::OVERRUN / 4), w = tid - st * (C::OVERRUN / 4);
-    *reinterpret_cast<unsigned *>(smem + st * C::STAGE + C::KCONST + 4 * w) = w == 0 ? 0x00003F80u : 0u;
-  } else if (C::ONES && tid >= 32 && tid < 32 + 2 * 4 * 2) {   // the (1, 0, 0, 0) pieces of V^T's row of ones
-    const int e = tid - 32, st = e >> 3, kc = (e >> 1) & 3, w = e & 1;
+    *reinterpret_cast<unsigned *>(smem + st * C::STAGE + C::KCONST + 4 * w) =
+        (w == 0 || (C::ONES && w == 4)) ? 0x00003F80u : 0u;
+  } else if (C::ONES && tid >= 32 && tid < 32 + 2 * 3 * 2) {   // the other three pieces of ones, 16 keys apart
+    const int e = tid - 32, st = e / 6, kc = 1 + (e % 6) / 2, w = e & 1;
     *reinterpret_cast<unsigned *>(smem + st * C::STAGE + C::VONE + kc * 16 * C::KROW + 4 * w) = w == 0 ? 0x00003F80u : 0u;
   }
 
