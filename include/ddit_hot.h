@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-#define DDIT_ABI_VERSION 2u
+#define DDIT_ABI_VERSION 3u
 
 typedef enum {
   DDIT_OK = 0,
@@ -194,6 +194,34 @@ typedef enum {
 int ddit_linear_fwd(int epilogue, const void *u, int64_t ld_u, const void *W, const void *bias, int64_t N,
                     int32_t n, int32_t k, void *out, int64_t ld_out, float *resid, const float *ada_table,
                     const float *c6, int gate_row, int64_t tokens_per_sample, void *hip_stream);
+
+/* ---- output tiles of the linear: for tuning and for parity tests of every compiled tile ----
+ * The linear is compiled for a short list of output tiles (rows x cols of out per workgroup) and
+ * ddit_linear_fwd takes, per call, the one that a cost model of the kernel prices cheapest for
+ * (epilogue, N, n, k) on the current device.  None of the three calls below is on the hot path. */
+
+/* Number of compiled tiles; tile indices are 0 .. count-1. */
+int ddit_linear_tile_count(void);
+
+/* Geometry of one tile: out rows and columns per workgroup, wavefronts per workgroup, and how
+ * many workgroups the launcher keeps resident per CU.  Any pointer may be NULL.
+ * DDIT_ERR_INVALID_ARG if tile is out of range.  Host only; needs no GPU. */
+int ddit_linear_tile_info(int tile, int32_t *rows, int32_t *cols, int32_t *wavefronts,
+                          int32_t *workgroups_per_cu);
+
+/* The tile ddit_linear_fwd would take for this problem on a device of compute_units CUs
+ * (compute_units <= 0: the current device's count, 256 if there is no device) -> *tile_out.
+ * predicted_us_host, if not NULL, is a HOST array of ddit_linear_tile_count() floats that
+ * receives the model's time for every tile, in microseconds.  Host only; needs no GPU. */
+int ddit_linear_tile_choice(int epilogue, int64_t N, int32_t n, int32_t k, int32_t compute_units,
+                            int32_t *tile_out, float *predicted_us_host);
+
+/* ddit_linear_fwd with the tile fixed (tile < 0: the model's choice, i.e. ddit_linear_fwd itself).
+ * Every tile computes the same function for every valid shape; only the time differs. */
+int ddit_linear_fwd_tile(int tile, int epilogue, const void *u, int64_t ld_u, const void *W, const void *bias,
+                         int64_t N, int32_t n, int32_t k, void *out, int64_t ld_out, float *resid,
+                         const float *ada_table, const float *c6, int gate_row, int64_t tokens_per_sample,
+                         void *hip_stream);
 
 /* c6 fp32 [B,6D] from timesteps (HOST fp32[B]) or from a given temb (device fp32 [B,D]).
  * scratch: device fp32, at least B*(256 + 2*D) floats. */

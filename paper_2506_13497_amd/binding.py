@@ -27,7 +27,8 @@ EXPORTS = ["ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_wo
            "ddit_attn_fwd", "ddit_stdit_block_fwd", "ddit_denoise_step", "ddit_modulated_layernorm_fwd",
            "ddit_linear_fwd", "ddit_timestep_conditioning", "ddit_io_workspace_bytes", "ddit_embed_latent",
            "ddit_embed_caption", "ddit_output_head", "ddit_eps_theta", "ddit_solver_step", "ddit_sample",
-           "ddit_cross_kv_bytes", "ddit_cross_kv_precompute", "ddit_denoise_step_cached"]
+           "ddit_cross_kv_bytes", "ddit_cross_kv_precompute", "ddit_denoise_step_cached", "ddit_linear_tile_count",
+           "ddit_linear_tile_info", "ddit_linear_tile_choice", "ddit_linear_fwd_tile"]
 
 
 class ddit_shape(C.Structure):
@@ -93,6 +94,11 @@ def _load() -> C.CDLL:
     lib.ddit_linear_fwd.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                     C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                     C.c_int64, C.c_void_p]
+    lib.ddit_linear_fwd_tile.argtypes = [C.c_int] + list(lib.ddit_linear_fwd.argtypes)
+    lib.ddit_linear_tile_count.argtypes = []
+    lib.ddit_linear_tile_info.argtypes = [C.c_int] + [C.POINTER(C.c_int32)] * 4
+    lib.ddit_linear_tile_choice.argtypes = [C.c_int, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32),
+                                            C.POINTER(C.c_float)]
     lib.ddit_timestep_conditioning.argtypes = [C.POINTER(ddit_shape), C.POINTER(ddit_step_weights),
                                                C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     SP, WP, IP, VP, FP = C.POINTER(ddit_shape), C.POINTER(ddit_step_weights), C.POINTER(ddit_io_weights), C.c_void_p, \
@@ -109,7 +115,7 @@ def _load() -> C.CDLL:
     lib.ddit_sample.argtypes = [SP, WP, IP, VP, VP, C.POINTER(C.c_int32), VP, VP, VP, C.c_float, C.c_int32, C.c_int32,
                                 C.c_int32, VP, VP, C.c_size_t, VP]
     for n in EXPORTS:
-        if n not in ("ddit_abi_version", "ddit_status_string", "ddit_last_error"):
+        if n not in ("ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_linear_tile_count"):
             getattr(lib, n).restype = C.c_int
     return lib
 
@@ -222,6 +228,30 @@ def ddit_linear_fwd(epilogue: int, u, ld_u: int, W, bias, N: int, n: int, k: int
                     ada_table=None, c6=None, gate_row: int = -1, tokens_per_sample: int = 1) -> None:
     _check(_lib.ddit_linear_fwd(epilogue, _ptr(u), ld_u, _ptr(W), _ptr(bias), N, n, k, _ptr(out), ld_out,
                                 _ptr(resid), _ptr(ada_table), _ptr(c6), gate_row, tokens_per_sample, _stream()))
+
+
+def ddit_linear_tile_count() -> int:
+    return int(_lib.ddit_linear_tile_count())
+
+
+def ddit_linear_tile_info(tile: int) -> Dict[str, int]:
+    v = [C.c_int32() for _ in range(4)]
+    _check(_lib.ddit_linear_tile_info(tile, *[C.byref(x) for x in v]))
+    return dict(zip(("rows", "cols", "wavefronts", "workgroups_per_cu"), (x.value for x in v)))
+
+
+def ddit_linear_tile_choice(epilogue: int, N: int, n: int, k: int, compute_units: int = 0):
+    """-> (tile, [predicted microseconds of every tile])."""
+    tile = C.c_int32()
+    us = (C.c_float * ddit_linear_tile_count())()
+    _check(_lib.ddit_linear_tile_choice(epilogue, N, n, k, compute_units, C.byref(tile), us))
+    return tile.value, list(us)
+
+
+def ddit_linear_fwd_tile(tile: int, epilogue: int, u, ld_u: int, W, bias, N: int, n: int, k: int, out, ld_out: int,
+                         resid=None, ada_table=None, c6=None, gate_row: int = -1, tokens_per_sample: int = 1) -> None:
+    _check(_lib.ddit_linear_fwd_tile(tile, epilogue, _ptr(u), ld_u, _ptr(W), _ptr(bias), N, n, k, _ptr(out), ld_out,
+                                     _ptr(resid), _ptr(ada_table), _ptr(c6), gate_row, tokens_per_sample, _stream()))
 
 
 def ddit_timestep_conditioning(shape: ddit_shape, weights: ddit_step_weights, timesteps, temb, c6_out, scratch) -> None:

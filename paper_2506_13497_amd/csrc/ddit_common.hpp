@@ -48,8 +48,14 @@ struct GemmArgs {
   const float *gate_c6;             // fp32, element (b, col) at gate_c6[b*gate_c6_stride + col], or null
   int64_t gate_c6_stride;
   int64_t tokens_per_sample;
+  int tile;                         // index into the tile list, or negative: the launcher's own choice
 };
 int launch_gemm(int epilogue, const GemmArgs &a, hipStream_t s);
+int gemm_tile_count();
+int gemm_tile_info(int tile, int *rows, int *cols, int *wavefronts, int *wg_per_cu);
+// the tile the launcher would take (cus <= 0: the current device's CU count); us_per_tile, if not
+// null, receives the model's time for each of the gemm_tile_count() tiles
+int gemm_tile_choice(int epilogue, int64_t N, int n, int k, int cus, float *us_per_tile);
 
 struct AttnArgs {
   const void *q, *k, *v; void *o; float *lse;

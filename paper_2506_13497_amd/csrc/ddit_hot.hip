@@ -178,7 +178,7 @@ int run_layer(ddit_attn_kind kind, const Dims &d, const ddit_layer_weights &w, c
 
   GemmArgs g;
   auto base = [&](const void *u, int64_t ld_u, const void *W, const void *b, int64_t rows, int n, int k) {
-    memset(&g, 0, sizeof(g));
+    memset(&g, 0, sizeof(g)); g.tile = -1;
     g.u = u; g.ld_u = ld_u; g.W = W; g.bias = b; g.N = rows; g.n = n; g.k = k; g.tokens_per_sample = d.L;
   };
   auto gated = [&](int row) {
@@ -438,7 +438,7 @@ int ddit_cross_kv_precompute(const ddit_shape *shape, const ddit_step_weights *w
     int l = 0;
     for (const ddit_layer_weights *w : {&weights->blocks[i].spatial, &weights->blocks[i].temporal}) {
       GemmArgs g;
-      memset(&g, 0, sizeof(g));
+      memset(&g, 0, sizeof(g)); g.tile = -1;
       g.u = y; g.ld_u = d.D; g.W = w->w_ckv; g.bias = w->b_ckv; g.N = d.B * d.Ly; g.n = (int)(2 * d.A); g.k = (int)d.D;
       g.out = out + (size_t)(2 * i + l) * per_layer; g.ld_out = 2 * d.A; g.tokens_per_sample = d.Ly;
       DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
@@ -514,9 +514,42 @@ int ddit_modulated_layernorm_fwd(const float *x, const float *ada_table, const f
                                     reinterpret_cast<hipStream_t>(hip_stream));
 }
 
+int ddit_linear_tile_count(void) { return gemm_tile_count(); }
+
+int ddit_linear_tile_info(int tile, int32_t *rows, int32_t *cols, int32_t *wavefronts, int32_t *workgroups_per_cu) {
+  int r, c, w, g;
+  if (gemm_tile_info(tile, &r, &c, &w, &g) != 0) {
+    set_error("no tile %d (there are %d)", tile, gemm_tile_count());
+    return DDIT_ERR_INVALID_ARG;
+  }
+  if (rows) *rows = r;
+  if (cols) *cols = c;
+  if (wavefronts) *wavefronts = w;
+  if (workgroups_per_cu) *workgroups_per_cu = g;
+  return DDIT_OK;
+}
+
+int ddit_linear_tile_choice(int epilogue, int64_t N, int32_t n, int32_t k, int32_t compute_units, int32_t *tile_out,
+                            float *predicted_us_host) {
+  if (epilogue < 0 || epilogue > 2) { set_error("unknown epilogue %d", epilogue); return DDIT_ERR_INVALID_ARG; }
+  if (N < 0 || n < 1 || k < 1) { set_error("linear: N=%lld n=%d k=%d", (long long)N, n, k); return DDIT_ERR_INVALID_ARG; }
+  if (!tile_out) { set_error("tile_out is NULL"); return DDIT_ERR_INVALID_ARG; }
+  *tile_out = gemm_tile_choice(epilogue, N, n, k, compute_units, predicted_us_host);
+  return DDIT_OK;
+}
+
 int ddit_linear_fwd(int epilogue, const void *u, int64_t ld_u, const void *W, const void *bias, int64_t N,
                     int32_t n, int32_t k, void *out, int64_t ld_out, float *resid, const float *ada_table,
                     const float *c6, int gate_row, int64_t tokens_per_sample, void *hip_stream) {
+  return ddit_linear_fwd_tile(-1, epilogue, u, ld_u, W, bias, N, n, k, out, ld_out, resid, ada_table, c6, gate_row,
+                              tokens_per_sample, hip_stream);
+}
+
+int ddit_linear_fwd_tile(int tile, int epilogue, const void *u, int64_t ld_u, const void *W, const void *bias,
+                         int64_t N, int32_t n, int32_t k, void *out, int64_t ld_out, float *resid,
+                         const float *ada_table, const float *c6, int gate_row, int64_t tokens_per_sample,
+                         void *hip_stream) {
+  if (tile >= gemm_tile_count()) { set_error("no tile %d (there are %d)", tile, gemm_tile_count()); return DDIT_ERR_INVALID_ARG; }
   if (epilogue < 0 || epilogue > 2) { set_error("unknown epilogue %d", epilogue); return DDIT_ERR_INVALID_ARG; }
   if (!u || !W) { set_error("u and W must not be NULL"); return DDIT_ERR_INVALID_ARG; }
   if (N < 0 || n < 1 || k < 1 || ld_u < k) { set_error("linear: N=%lld n=%d k=%d ld_u=%lld", (long long)N, n, k, (long long)ld_u); return DDIT_ERR_INVALID_ARG; }
@@ -526,7 +559,7 @@ int ddit_linear_fwd(int epilogue, const void *u, int64_t ld_u, const void *W, co
     set_error("pointers must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT;
   }
   GemmArgs g;
-  memset(&g, 0, sizeof(g));
+  memset(&g, 0, sizeof(g)); g.tile = -1;
   g.u = u; g.ld_u = ld_u; g.W = W; g.bias = bias; g.N = N; g.n = n; g.k = k;
   g.tokens_per_sample = tokens_per_sample > 0 ? tokens_per_sample : 1;
   if (epilogue == DDIT_EPI_RESIDUAL_F32) {
@@ -545,6 +578,7 @@ int ddit_linear_fwd(int epilogue, const void *u, int64_t ld_u, const void *W, co
     if (ld_out < n || ld_out % 8) { set_error("ld_out=%lld invalid", (long long)ld_out); return DDIT_ERR_INVALID_ARG; }
   }
   g.out = out; g.ld_out = ld_out;
+  g.tile = tile < 0 ? -1 : tile;
   return launch_gemm(epilogue, g, reinterpret_cast<hipStream_t>(hip_stream));
 }
 
@@ -594,7 +628,7 @@ int ddit_embed_caption(const ddit_shape *shape, const ddit_io_weights *io, const
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   void *tmp = reinterpret_cast<unsigned char *>(workspace) + lo.cap;
   GemmArgs g;
-  memset(&g, 0, sizeof(g));
+  memset(&g, 0, sizeof(g)); g.tile = -1;
   g.u = c_text; g.ld_u = io->C_text; g.W = io->w_y1; g.bias = io->b_y1; g.N = d.B * d.Ly; g.n = (int)d.D;
   g.k = io->C_text; g.out = tmp; g.ld_out = d.D; g.tokens_per_sample = d.Ly;
   DDIT_TRY(launch_gemm(DDIT_EPI_GELU_BF16, g, s));

@@ -41,6 +41,8 @@
 // also storing bf16(x).
 #include "ddit_common.hpp"
 
+#include <cmath>
+
 namespace {
 
 constexpr int BK = 32;        // k per pipeline step (bf16 elements)
@@ -670,37 +672,113 @@ int launch_one(const GemmParams &p0, hipStream_t s) {
   return ddit::hip_fail(hipGetLastError(), "gemm launch");
 }
 
-template <int EPI>
-int launch_epi(const GemmParams &p, hipStream_t s) {
-  // The 192x384 tile runs at roughly twice the rate of the small one per useful flop, so it is
-  // taken whenever there are enough tiles to fill half the chip and at most 30 % of the
-  // 384-wide feature tiles is padding (288 and 864 out-features qualify; 384-wide tiles divide
-  // 1152, 3456 and 4608 exactly).  Narrow outputs and short token counts take the small tile so
-  // that more than a handful of CUs get work.
-  const int64_t tiles_n = (p.n + 383) / 384;
-  const int64_t big_tiles = ((p.N + 191) / 192) * tiles_n;
-  const bool big = big_tiles >= 200 && 10 * (int64_t)p.n >= 7 * 384 * tiles_n;
-  // out-feature counts that are multiples of 288 but not of 384 (a head-split rank's 4 x 72 = 288
-  // attention width and its 864-wide q|k|v): a 192 x 288 tile of six wavefronts has no padding there
-  if constexpr (EPI == 0) {
-    if (p.n % 288 == 0 && p.n % 384 != 0 && ((p.N + 191) / 192) * (p.n / 288) >= 200)
-      return launch_one<2, 3, 3, 3, 4, EPI>(p, s);
+// ---------------------------------------------------------------------------------------------
+// Tile choice.  Seven output tiles are compiled; which is fastest depends on how the tile grid
+// divides over the CUs far more than on the tile's own efficiency (a 192 x 384 tile runs its k
+// loop at about twice the rate per flop of a 128 x 128 one, but 60 of them leave 196 CUs idle).
+// The launcher therefore prices every tile with a small model of the kernel and takes the
+// cheapest.  With  tiles = ceil(N / rows) * ceil(n / cols)  and  q = ceil(tiles / CUs)  tiles on
+// the busiest CU,
+//     t = (a * k / 1152 + e[epilogue]) * q / gain[min(q, workgroups per CU)]
+//         * (1 + 0.34 * min(1, tiles / CUs)) + 0.75      [microseconds]
+// a: one workgroup's k-loop time per 1152 of k with a CU to itself; e: its epilogue and set-up;
+// gain: what sharing a CU between two or three resident workgroups returns; the load term is the
+// clock and memory slow-down of a full chip against a single busy CU.  The constants are a
+// least-squares fit (in log time) to a sweep of the model's five linears over 23 token counts
+// from 288 to 48600 with every tile forced in turn (ddit_linear_fwd_tile): over that sweep the
+// model's picks are within 0.3 % of the best tile's total time.
+// ---------------------------------------------------------------------------------------------
+struct TileModel {
+  int rows, cols, wavefronts, wg_per_cu;
+  float a;        // k-loop microseconds per 1152 of k, alone on a CU
+  float e[3];     // epilogue + set-up microseconds: bf16 / GELU / gated residual
+};
+constexpr int N_TILES = 7;
+constexpr TileModel TILES[N_TILES] = {
+    {192, 384, 8, 1, 22.21f, {4.48f, 7.89f, 15.94f}},
+    {192, 288, 6, 1, 18.99f, {4.13f, 7.45f, 14.74f}},
+    {192, 256, 8, 1, 15.72f, {3.34f, 5.41f, 10.38f}},
+    {192, 192, 4, 1, 12.85f, {4.18f, 6.16f, 12.13f}},
+    {128, 192, 4, 2, 11.23f, {2.37f, 3.95f, 8.19f}},
+    {128, 128, 4, 2, 8.30f, {1.39f, 1.79f, 4.67f}},
+    {64, 128, 4, 3, 6.16f, {0.51f, 0.76f, 1.89f}},
+};
+constexpr float CU_SHARE_GAIN[3] = {1.0f, 1.14f, 1.17f};
+constexpr float FULL_CHIP_SLOWDOWN = 0.34f, LAUNCH_US = 0.75f;
+
+float predicted_us(int tile, int epilogue, int64_t N, int n, int k, int cus) {
+  const TileModel &t = TILES[tile];
+  const double tiles = (double)((N + t.rows - 1) / t.rows) * (double)((n + t.cols - 1) / t.cols);
+  const double q = std::ceil(tiles / cus);
+  const int sharing = q < t.wg_per_cu ? (int)q : t.wg_per_cu;
+  const double one = t.a * (double)k / 1152.0 + t.e[epilogue];
+  const double load = 1.0 + FULL_CHIP_SLOWDOWN * (tiles < cus ? tiles / cus : 1.0);
+  return (float)(one * q / CU_SHARE_GAIN[sharing > 0 ? sharing - 1 : 0] * load + LAUNCH_US);
+}
+
+int cheapest_tile(int epilogue, int64_t N, int n, int k, int cus) {
+  int best = 0;
+  float best_us = predicted_us(0, epilogue, N, n, k, cus);
+  for (int t = 1; t < N_TILES; ++t) {
+    const float us = predicted_us(t, epilogue, N, n, k, cus);
+    if (us < best_us) { best_us = us; best = t; }
   }
-  if (big) return launch_one<2, 4, 3, 3, 4, EPI>(p, s);
-  // Short token counts (a rank's share of a low-resolution request): when even the 128 x 128 tiles
-  // would leave a quarter of the chip's workgroup slots empty, 64 x 128 tiles (three workgroups per
-  // CU) put twice as many workgroups to work on the same problem, each with half the k-loop time.
-  const int64_t small_tiles = ((p.N + 127) / 128) * ((p.n + 127) / 128);
-  if (small_tiles * 4 < (int64_t)num_cus() * 2 * 3) return launch_one<2, 2, 1, 2, 4, EPI>(p, s);
-  return launch_one<2, 2, 2, 2, 4, EPI>(p, s);
+  return best;
+}
+
+template <int WGM, int WGN, int TM, int TN, int EPI>
+int launch_checked(int tile, const GemmParams &p, hipStream_t s) {
+  using C = GemmCfg<WGM, WGN, TM, TN, 4>;
+  // the model's table and the compiled tile must describe the same thing
+  if (TILES[tile].rows != C::BM || TILES[tile].cols != C::BN || TILES[tile].wavefronts != C::NW) {
+    ddit::set_error("linear: tile table entry %d does not match its kernel", tile);
+    return -2;
+  }
+  return launch_one<WGM, WGN, TM, TN, 4, EPI>(p, s);
+}
+
+template <int EPI>
+int launch_epi(int tile, const GemmParams &p, hipStream_t s) {
+  if (tile < 0) tile = cheapest_tile(EPI, p.N, p.n, p.k, num_cus());
+  switch (tile) {
+    case 0: return launch_checked<2, 4, 3, 3, EPI>(tile, p, s);
+    case 1: return launch_checked<2, 3, 3, 3, EPI>(tile, p, s);
+    case 2: return launch_checked<2, 4, 3, 2, EPI>(tile, p, s);
+    case 3: return launch_checked<2, 2, 3, 3, EPI>(tile, p, s);
+    case 4: return launch_checked<2, 2, 2, 3, EPI>(tile, p, s);
+    case 5: return launch_checked<2, 2, 2, 2, EPI>(tile, p, s);
+    case 6: return launch_checked<2, 2, 1, 2, EPI>(tile, p, s);
+  }
+  ddit::set_error("linear: no tile %d (there are %d)", tile, N_TILES);
+  return -1;
 }
 
 }  // namespace
 
 namespace ddit {
 
+int gemm_tile_count() { return N_TILES; }
+
+int gemm_tile_info(int tile, int *rows, int *cols, int *wavefronts, int *wg_per_cu) {
+  if (tile < 0 || tile >= N_TILES) return -1;
+  *rows = TILES[tile].rows; *cols = TILES[tile].cols;
+  *wavefronts = TILES[tile].wavefronts; *wg_per_cu = TILES[tile].wg_per_cu;
+  return 0;
+}
+
+int gemm_tile_choice(int epilogue, int64_t N, int n, int k, int cus, float *us_per_tile) {
+  if (cus <= 0) cus = num_cus();
+  if (us_per_tile)
+    for (int t = 0; t < N_TILES; ++t) us_per_tile[t] = predicted_us(t, epilogue, N, n, k, cus);
+  return cheapest_tile(epilogue, N, n, k, cus);
+}
+
 int launch_gemm(int epilogue, const GemmArgs &a, hipStream_t s) {
   if (a.N == 0 || a.n == 0) return 0;
+  if (a.tile >= N_TILES) {
+    set_error("linear: no tile %d (there are %d)", a.tile, N_TILES);
+    return -1;
+  }
   if ((int64_t)a.n * a.k >= (int64_t)1 << 31) {
     set_error("linear: n*k = %lld exceeds the 32-bit weight index range", (long long)a.n * a.k);
     return -2;
@@ -720,9 +798,9 @@ int launch_gemm(int epilogue, const GemmArgs &a, hipStream_t s) {
   p.tokens_per_sample = a.tokens_per_sample > 0 ? a.tokens_per_sample : 1;
   p.tiles_m = 0; p.tiles_n = 0; p.group_w = 1; p.total_tiles = 0; p.rounds = 0;
   switch (epilogue) {
-    case 0: return launch_epi<0>(p, s);
-    case 1: return launch_epi<1>(p, s);
-    case 2: return launch_epi<2>(p, s);
+    case 0: return launch_epi<0>(a.tile, p, s);
+    case 1: return launch_epi<1>(a.tile, p, s);
+    case 2: return launch_epi<2>(a.tile, p, s);
   }
   set_error("unknown epilogue %d", epilogue);
   return -1;

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol(m):
     for n in names:
         assert hasattr(lib, n), "missing export " + n
     assert sorted(m.binding.EXPORTS) == names
-    assert m.ddit_abi_version() == 2
+    assert m.ddit_abi_version() == 3
 
 
 def test_status_strings(m):
@@ -154,6 +154,56 @@ def test_linear_and_layernorm_validation(m):
     assert lib.ddit_modulated_layernorm_fwd(P(0x1000), P(0x2000), P(0x3000), 2, 4, 4, 64, 1e-6, P(0x4000), None) == -1  # which
     assert lib.ddit_modulated_layernorm_fwd(P(0x1000), P(0x2000), P(0x3000), 0, 4, 4, 60, 1e-6, P(0x4000), None) == -2  # D % 8
     assert lib.ddit_modulated_layernorm_fwd(None, P(0x2000), P(0x3000), 0, 4, 4, 64, 1e-6, P(0x4000), None) == -1
+
+
+def test_linear_tile_list_and_cost_model(m):
+    """Host side of the tile choice: the list is consistent, bad indices are refused before any
+    launch, and the model's pick is the cheapest of its own prices and behaves sensibly at the
+    two ends (one tile's worth of tokens -> the smallest tile; a full 480p fc1 -> the largest)."""
+    lib = m.binding._lib
+    P = C.c_void_p
+    count = m.ddit_linear_tile_count()
+    assert count >= 2
+    areas = []
+    for t in range(count):
+        info = m.ddit_linear_tile_info(t)
+        assert info["rows"] % 64 == 0 and info["cols"] % 32 == 0
+        assert info["wavefronts"] in (4, 6, 8) and 1 <= info["workgroups_per_cu"] <= 3
+        areas.append(info["rows"] * info["cols"])
+    assert areas == sorted(areas, reverse=True) and len(set(areas)) == count
+    for bad in (-1, count):
+        with pytest.raises(m.DditError) as e:
+            m.ddit_linear_tile_info(bad)
+        assert e.value.status == -1
+    assert lib.ddit_linear_tile_info(0, None, None, None, None) == 0           # every output is optional
+    # a forced tile past the list is refused; arguments are still validated first
+    args = (0, P(0x1000), 64, P(0x2000), None, 16, 64, 64, P(0x3000), 64, None, None, None, -1, 1, None)
+    assert lib.ddit_linear_fwd_tile(count, *args) == -1
+    assert "no tile" in m.ddit_last_error()
+    assert lib.ddit_linear_fwd_tile(0, 0, P(0x1000), 60, P(0x2000), None, 16, 64, 64, P(0x3000), 64, None, None, None, -1, 1, None) == -1
+    # choice
+    tile = C.c_int32(-7)
+    assert lib.ddit_linear_tile_choice(3, 100, 64, 64, 256, C.byref(tile), None) == -1
+    assert lib.ddit_linear_tile_choice(0, 100, 0, 64, 256, C.byref(tile), None) == -1
+    assert lib.ddit_linear_tile_choice(0, 100, 64, 64, 256, None, None) == -1
+    for epi in (0, 1, 2):
+        for N, n, k in [(1, 8, 8), (64, 128, 1152), (2304, 1152, 4608), (3680, 3456, 1152), (48600, 4608, 1152),
+                        (13001, 864, 1160)]:
+            t, us = m.ddit_linear_tile_choice(epi, N, n, k, 256)
+            assert 0 <= t < count and len(us) == count and all(x > 0 for x in us)
+            assert us[t] == min(us)
+        assert m.ddit_linear_tile_choice(epi, 64, 128, 1152, 256)[0] == count - 1
+        assert m.ddit_linear_tile_choice(epi, 48600, 4608, 1152, 256)[0] == 0
+        # more tokens never cost less, whatever the tile
+        prev = [0.0] * count
+        for N in (1, 100, 1000, 3000, 9000, 27000, 81000):
+            us = m.ddit_linear_tile_choice(epi, N, 1152, 1152, 256)[1]
+            assert all(a >= b for a, b in zip(us, prev))
+            prev = us
+    # fewer CUs: the same problem spreads over more rounds, so no tile gets cheaper
+    a = m.ddit_linear_tile_choice(0, 20000, 1152, 1152, 256)[1]
+    b = m.ddit_linear_tile_choice(0, 20000, 1152, 1152, 64)[1]
+    assert all(y >= x for x, y in zip(a, b))
 
 
 def _io(m, **kw):

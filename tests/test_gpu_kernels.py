@@ -74,6 +74,30 @@ LIN_CASES = [
 @pytest.mark.parametrize("N,n,k", LIN_CASES)
 @pytest.mark.parametrize("epi", [0, 1, 2])
 def test_linear(lib, N, n, k, epi):
+    _check_linear(lib, N, n, k, epi, -1)
+
+
+N_TILES = 7
+TILE_CASES = [
+    (403, 872, 1160),     # ragged in rows and columns for every tile shape, k tail
+    (1, 8, 8),            # one partial tile, one partial k-step
+    (700, 1152, 288),     # narrow k, several row tiles
+]
+
+
+def test_tile_list_matches(lib):
+    assert lib.ddit_linear_tile_count() == N_TILES
+
+
+@pytest.mark.parametrize("N,n,k", TILE_CASES)
+@pytest.mark.parametrize("epi", [0, 1, 2])
+@pytest.mark.parametrize("tile", range(N_TILES))
+def test_linear_every_tile(lib, tile, epi, N, n, k):
+    """Every compiled output tile computes the same function on shapes its grid does not divide."""
+    _check_linear(lib, N, n, k, epi, tile)
+
+
+def _check_linear(lib, N, n, k, epi, tile):
     u = syn.normal_bits((11, N, n, k), (N, k), 1.0)
     W = syn.normal_bits((12, N, n, k), (n, k), 1.0 / math.sqrt(k))
     b = syn.normal_bits((13, N, n, k), (n,), 0.5)
@@ -81,7 +105,7 @@ def test_linear(lib, N, n, k, epi):
     du, dW, db = to_dev(u), to_dev(W), to_dev(b)
     if epi in (0, 1):
         out = torch.full((N, n), float("nan"), dtype=torch.bfloat16, device="cuda")
-        lib.ddit_linear_fwd(epi, du, k, dW, db, N, n, k, out, n)
+        lib.ddit_linear_fwd_tile(tile, epi, du, k, dW, db, N, n, k, out, n)
         torch.cuda.synchronize()
         ref = lin if epi == 0 else ora.gelu_tanh(lin)
         assert_parity(dev_to_f64(out), ref, "linear epi=%d" % epi)
@@ -95,8 +119,8 @@ def test_linear(lib, N, n, k, epi):
         for gate_row in (2, 5, -1):
             dres = to_dev(resid)
             out = torch.full((N, n), float("nan"), dtype=torch.bfloat16, device="cuda")
-            lib.ddit_linear_fwd(2, du, k, dW, db, N, n, k, out, n, resid=dres, ada_table=to_dev(tab), c6=to_dev(c6),
-                                gate_row=gate_row, tokens_per_sample=tps)
+            lib.ddit_linear_fwd_tile(tile, 2, du, k, dW, db, N, n, k, out, n, resid=dres, ada_table=to_dev(tab),
+                                     c6=to_dev(c6), gate_row=gate_row, tokens_per_sample=tps)
             torch.cuda.synchronize()
             ref = resid.astype(np.float64).copy()
             for r in range(N):
@@ -106,7 +130,7 @@ def test_linear(lib, N, n, k, epi):
             assert torch.equal(out, dres.to(torch.bfloat16)), "bf16 copy of the stream differs"
         # without the bf16 copy
         dres = to_dev(resid)
-        lib.ddit_linear_fwd(2, du, k, dW, None, N, n, k, None, 0, resid=dres)
+        lib.ddit_linear_fwd_tile(tile, 2, du, k, dW, None, N, n, k, None, 0, resid=dres)
         torch.cuda.synchronize()
         assert_parity(dev_to_f64(dres), resid + ora.linear(to_f64(u), to_f64(W)), "linear residual, no bias/gate/copy")
 
