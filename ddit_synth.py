@@ -139,8 +139,22 @@ def make_layer_weights(sh: Shape, base: int, block: int, kind: str,
     return out
 
 
-def make_block_weights(sh: Shape, base: int, block: int, **kw) -> Dict[str, Dict[str, np.ndarray]]:
-    return {k: make_layer_weights(sh, base, block, k, **kw) for k in ("spatial", "temporal")}
+def make_qk_norm_scales(sh: Shape, base: int, block: int, kind: str, spread: float = 0.2) -> Dict[str, np.ndarray]:
+    """Per-head RMS-norm scales g_q, g_k [dh] of one layer's self-attention: bf16 bit patterns of
+    1 + spread * N(0,1) draws (a trained norm's scales sit around one)."""
+    out = {}
+    for tid, name in enumerate(("g_q", "g_k")):
+        g = _rng(base, block, 70 + 100 * _KIND_ID[kind] + tid)
+        out[name] = f32_to_bf16_bits((1.0 + spread * g.standard_normal(size=(sh.dh,), dtype=np.float32)).astype(np.float32))
+    return out
+
+
+def make_block_weights(sh: Shape, base: int, block: int, qk_norm: bool = False, **kw) -> Dict[str, Dict[str, np.ndarray]]:
+    out = {k: make_layer_weights(sh, base, block, k, **kw) for k in ("spatial", "temporal")}
+    if qk_norm:
+        for k in out:
+            out[k].update(make_qk_norm_scales(sh, base, block, k))
+    return out
 
 
 def make_step_weights(sh: Shape, base: int, w_std: float = 0.02) -> Dict[str, np.ndarray]:

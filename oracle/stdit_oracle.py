@@ -33,7 +33,14 @@ Where the paper is silent (it never writes the block down), the readings are:
   * the timestep feature is [cos(t f_i), sin(t f_i)], f_i = 10000^(-i/128), i < 128,
     followed by Linear(256->D), SiLU, Linear(D->D);
   * the attention width A = H d_h may be smaller than D (one rank's share of a
-    head-split run): W_qkv is [3A, D], W_o is [D, A].
+    head-split run): W_qkv is [3A, D], W_o is [D, A];
+  * two options the released model of Table 1 has and the paper does not mention, both
+    off unless asked for: (i) per-head RMS normalisation of the self-attention queries
+    and keys, u / sqrt(mean(u^2) + eps) * g over the d_h elements of a head with learned
+    g_q, g_k in R^{d_h} per layer (eps = the LayerNorm's), not applied in
+    cross-attention; (ii) rotary position embedding of the TEMPORAL self-attention's
+    queries and keys (after the normalisation), position = frame index, element pairs
+    (2i, 2i+1) rotated by the angle  t * 10000^(-2i/d_h).
 
 Tensors: x [B,T,S,D] with token index ((b T + t) S + s); y [B,Ly,D]; weights [out,in]
 so that linear(u) = u W^T + b.  All arguments and results are float64 numpy arrays.
@@ -43,7 +50,10 @@ routines of another package for attention / LayerNorm / GELU / SiLU, closed form
 (uniform keys, one dominant key, T = 1, zero gates), invariances (key shift, frame
 permutation, locality per axis, mask independence, batch independence), composition,
 and the parameter count against Table 1.  The paper prints no activation value, so
-absolute values are pinned only by those.
+absolute values are pinned only by those.  The two options: another package's RMS norm,
+unit mean square and scale invariance; rotation written as complex multiplication, the
+relative-position property of the scores, norm preservation, identity at position 0,
+and a brute-force temporal layer.
 """
 from __future__ import annotations
 
@@ -84,6 +94,28 @@ def gelu_tanh(u):
 
 def silu(u):
     return u / (1.0 + np.exp(-u))
+
+
+def rms_norm(u, g, eps=LN_EPS):
+    """u / sqrt(mean(u^2) + eps) * g over the last axis."""
+    return u / np.sqrt((u ** 2).mean(axis=-1, keepdims=True) + eps) * g
+
+
+def rotary(u, pos, theta=10000.0):
+    """Rotary position embedding over the last axis (even length d): the pair
+    (u[2i], u[2i+1]) is rotated by the angle pos * theta^(-2i/d).
+    pos: array broadcastable to u.shape[:-1]."""
+    d = u.shape[-1]
+    if d % 2:
+        raise ValueError("rotary embedding needs an even width")
+    w = theta ** (-2.0 * np.arange(d // 2, dtype=np.float64) / d)
+    ang = np.asarray(pos, dtype=np.float64)[..., None] * w
+    c, s = np.cos(ang), np.sin(ang)
+    a, b = u[..., 0::2], u[..., 1::2]
+    out = np.empty(np.broadcast_shapes(u.shape, c.shape[:-1] + (d,)), dtype=np.float64)
+    out[..., 0::2] = a * c - b * s
+    out[..., 1::2] = b * c + a * s
+    return out
 
 
 def softmax_rows(s):
@@ -172,8 +204,10 @@ def split_modulation(table, c6_b, D):
     return {n: m[i] for i, n in enumerate(ADA_NAMES)}
 
 
-def layer_fwd(kind, x, y, valid_len, c6, w, H, dh, taps=None):
-    """One layer of kind 'spatial' or 'temporal'.
+def layer_fwd(kind, x, y, valid_len, c6, w, H, dh, taps=None, rope_temporal=False):
+    """One layer of kind 'spatial' or 'temporal'.  If w holds 'g_q' and 'g_k' ([dh]) the
+    self-attention's q and k are RMS-normalised per head; with rope_temporal the temporal
+    layer's q and k get the rotary embedding of their frame index.
 
     x [B,T,S,D], y [B,Ly,D], valid_len [B] or None, c6 [B,6D], w: dict of fp64 arrays
     (w_qkv,b_qkv,w_o,b_o,w_cq,b_cq,w_ckv,b_ckv,w_co,b_co,w_fc1,b_fc1,w_fc2,b_fc2,
@@ -192,6 +226,11 @@ def layer_fwd(kind, x, y, valid_len, c6, w, H, dh, taps=None):
     xh = modulate(layer_norm(x), per_sample("shift_msa"), per_sample("scale_msa"))
     qkv = linear(xh, w["w_qkv"], w["b_qkv"])                      # [B,T,S,3A]
     q, k, v = (qkv[..., i * A:(i + 1) * A].reshape(B, T, S, H, dh) for i in range(3))
+    if "g_q" in w:
+        q, k = rms_norm(q, w["g_q"]), rms_norm(k, w["g_k"])
+    if rope_temporal and kind == "temporal":
+        frame = np.arange(T, dtype=np.float64)[None, :, None, None]          # [1,T,1,1]
+        q, k = rotary(q, frame), rotary(k, frame)
     if kind == "spatial":
         o, lse = spatial_attention(q, k, v)
     elif kind == "temporal":
@@ -221,12 +260,12 @@ def layer_fwd(kind, x, y, valid_len, c6, w, H, dh, taps=None):
     return x
 
 
-def block_fwd(x, y, valid_len, c6, wblock, H, dh, taps=None):
+def block_fwd(x, y, valid_len, c6, wblock, H, dh, taps=None, rope_temporal=False):
     """A block = spatial layer followed by temporal layer.  wblock = {'spatial':..,'temporal':..}."""
     ts = None if taps is None else taps.setdefault("spatial", {})
     tt = None if taps is None else taps.setdefault("temporal", {})
-    x = layer_fwd("spatial", x, y, valid_len, c6, wblock["spatial"], H, dh, ts)
-    x = layer_fwd("temporal", x, y, valid_len, c6, wblock["temporal"], H, dh, tt)
+    x = layer_fwd("spatial", x, y, valid_len, c6, wblock["spatial"], H, dh, ts, rope_temporal=rope_temporal)
+    x = layer_fwd("temporal", x, y, valid_len, c6, wblock["temporal"], H, dh, tt, rope_temporal=rope_temporal)
     return x
 
 
@@ -248,14 +287,14 @@ def conditioning(temb, sw):
     return linear(silu(temb), sw["w_ada"], sw["b_ada"])
 
 
-def denoise_step(x, y, valid_len, t, sw, blocks, H, dh, temb=None):
+def denoise_step(x, y, valid_len, t, sw, blocks, H, dh, temb=None, rope_temporal=False):
     """One denoising step in token space: conditioning from the timestep (or from a given
     temb [B,D]), then the blocks in order.  blocks: list of {'spatial':..,'temporal':..}."""
     if temb is None:
         temb = timestep_embedding(t, sw)
     c6 = conditioning(temb, sw)
     for wb in blocks:
-        x = block_fwd(x, y, valid_len, c6, wb, H, dh)
+        x = block_fwd(x, y, valid_len, c6, wb, H, dh, rope_temporal=rope_temporal)
     return x
 
 

@@ -89,3 +89,25 @@ def layer_norm_row(u, eps):
 def linear_row(u, W, b):
     """u [in], W [out][in], b [out]."""
     return [sum(W[o][i] * u[i] for i in range(len(u))) + b[o] for o in range(len(W))]
+
+
+def rms_norm_row(u, g, eps):
+    """u, g lists -> u / sqrt(mean(u^2) + eps) * g, element by element."""
+    ms = 0.0
+    for a in u:
+        ms += a * a
+    ms /= len(u)
+    return [a / math.sqrt(ms + eps) * w for a, w in zip(u, g)]
+
+
+def rotary_row(u, pos, theta=10000.0):
+    """Rotary embedding of one vector, written as complex multiplication: the pair
+    (u[2i], u[2i+1]) read as the complex number u[2i] + 1j u[2i+1] is multiplied by
+    exp(1j pos theta^(-2i/d))."""
+    import cmath
+    d = len(u)
+    out = []
+    for i in range(d // 2):
+        z = complex(u[2 * i], u[2 * i + 1]) * cmath.exp(1j * pos * theta ** (-2.0 * i / d))
+        out += [z.real, z.imag]
+    return out

@@ -402,6 +402,99 @@ class TestStep:
 
 
 # --------------------------------------------------------------- planted mistakes
+class TestQkNormRotary:
+    """The two optional pieces: per-head RMS normalisation of q and k, and the rotary
+    embedding of the temporal layer's q and k."""
+
+    def test_rms_norm_vs_torch_and_loops(self):
+        u, g = _rand((5, 3, 8), 1) * 2 + 0.3, _rand((8,), 2) * 0.2 + 1
+        got = ora.rms_norm(u, g, 1e-6)
+        ref = F.rms_norm(torch.from_numpy(u), (8,), torch.from_numpy(g), 1e-6).numpy()
+        np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(got[2, 1], bf.rms_norm_row(u[2, 1].tolist(), g.tolist(), 1e-6), atol=1e-12)
+
+    def test_rms_norm_closed_forms(self):
+        # (3, 4): mean square 12.5
+        np.testing.assert_allclose(ora.rms_norm(np.array([3.0, 4.0]), np.ones(2), 0.0), np.array([3.0, 4.0]) / math.sqrt(12.5))
+        u = _rand((7, 12), 3) + 0.7                                  # non-zero mean: not a LayerNorm
+        n = ora.rms_norm(u, np.ones(12), 0.0)
+        np.testing.assert_allclose((n ** 2).mean(-1), 1.0, atol=1e-12)
+        np.testing.assert_allclose(ora.rms_norm(5.0 * u, np.ones(12), 0.0), n, atol=1e-12)     # scale invariant
+        assert abs(n.mean(-1)).max() > 0.1                                                     # mean is kept
+        # eps enters under the root, added to the mean square
+        np.testing.assert_allclose(ora.rms_norm(np.array([2.0, 0.0]), np.ones(2), 2.0), np.array([1.0, 0.0]))
+
+    def test_rotary_is_complex_multiplication(self):
+        u = _rand((4, 6, 10), 4)
+        pos = np.arange(6, dtype=np.float64)[None, :] * np.ones((4, 1))
+        got = ora.rotary(u, pos)
+        w = 10000.0 ** (-2.0 * np.arange(5) / 10)
+        z = (u[..., 0::2] + 1j * u[..., 1::2]) * np.exp(1j * pos[..., None] * w)
+        np.testing.assert_allclose(got[..., 0::2], z.real, atol=1e-12)
+        np.testing.assert_allclose(got[..., 1::2], z.imag, atol=1e-12)
+        for b, t in ((0, 0), (1, 3), (3, 5)):
+            np.testing.assert_allclose(got[b, t], bf.rotary_row(u[b, t].tolist(), float(t)), atol=1e-12)
+
+    def test_rotary_quarter_turn_and_frequency_ladder(self):
+        # d = 4: pair 0 turns by pos, pair 1 by pos / 100
+        e0 = np.array([1.0, 0.0, 0.0, 0.0])
+        np.testing.assert_allclose(ora.rotary(e0, math.pi / 2), [0.0, 1.0, 0.0, 0.0], atol=1e-15)
+        e2 = np.array([0.0, 0.0, 1.0, 0.0])
+        np.testing.assert_allclose(ora.rotary(e2, 100 * math.pi / 2), [0.0, 0.0, 0.0, 1.0], atol=1e-12)
+        np.testing.assert_allclose(ora.rotary(e2, math.pi / 2), [0, 0, math.cos(math.pi / 200), math.sin(math.pi / 200)], atol=1e-15)
+
+    def test_rotary_identity_norm_and_relative_position(self):
+        q, k = _rand((9, 8), 5), _rand((9, 8), 6)
+        np.testing.assert_allclose(ora.rotary(q, np.zeros(9)), q, atol=0)
+        pos = np.arange(9.0)
+        rq, rk = ora.rotary(q, pos), ora.rotary(k, pos)
+        np.testing.assert_allclose((rq ** 2).sum(-1), (q ** 2).sum(-1), rtol=1e-12)
+        # scores depend on the positions only through their difference
+        s0 = rq @ rk.T
+        s1 = ora.rotary(q, pos + 37.0) @ ora.rotary(k, pos + 37.0).T
+        np.testing.assert_allclose(s0, s1, atol=1e-10)
+        assert rel_fro(s0, q @ k.T) > 0.05                      # and it does something
+
+    def test_temporal_layer_with_both_options_vs_loops(self):
+        sh = TINY
+        w, x, y, c6 = _tiny_layer(3)
+        w = dict(w, g_q=_rand((sh.dh,), 11) * 0.3 + 1, g_k=_rand((sh.dh,), 12) * 0.3 + 1)
+        taps = {}
+        out = ora.layer_fwd("temporal", x, y, None, c6, w, sh.H, sh.dh, taps, rope_temporal=True)
+        plain = {}
+        ora.layer_fwd("temporal", x, y, None, c6, {n: v for n, v in w.items() if n not in ("g_q", "g_k")}, sh.H, sh.dh, plain)
+        # q, k of the taps = loops over the untouched projections: norm first, rotation second
+        for name, g in (("q", w["g_q"]), ("k", w["g_k"])):
+            for b in range(sh.B):
+                for t in range(sh.T):
+                    for s_ in range(sh.S):
+                        for h in range(sh.H):
+                            ref = bf.rotary_row(bf.rms_norm_row(plain[name][b, t, s_, h].tolist(), g.tolist(), 1e-6), float(t))
+                            np.testing.assert_allclose(taps[name][b, t, s_, h], ref, atol=1e-12)
+        np.testing.assert_allclose(taps["v"], plain["v"], atol=0)
+        o = np.array(bf.temporal(taps["q"].tolist(), taps["k"].tolist(), taps["v"].tolist()))
+        np.testing.assert_allclose(taps["o"], o, atol=1e-12)
+        # cross-attention keeps its plain projections of the stream and the text
+        np.testing.assert_allclose(taps["qc"].reshape(sh.B, sh.T, sh.S, -1), ora.linear(taps["x_after_attn"], w["w_cq"], w["b_cq"]), atol=1e-12)
+        np.testing.assert_allclose(taps["kc"].reshape(sh.B, sh.Ly, -1), ora.linear(y, w["w_ckv"], w["b_ckv"])[..., :sh.A], atol=1e-12)
+        assert rel_fro(out, ora.layer_fwd("temporal", x, y, None, c6, w, sh.H, sh.dh)) > 1e-4   # rotation matters
+
+    def test_spatial_layer_normalises_but_never_rotates(self):
+        sh = TINY
+        w, x, y, c6 = _tiny_layer(4)
+        wn = dict(w, g_q=_rand((sh.dh,), 13) * 0.3 + 1, g_k=_rand((sh.dh,), 14) * 0.3 + 1)
+        a = ora.layer_fwd("spatial", x, y, None, c6, wn, sh.H, sh.dh, rope_temporal=True)
+        b = ora.layer_fwd("spatial", x, y, None, c6, wn, sh.H, sh.dh, rope_temporal=False)
+        np.testing.assert_allclose(a, b, atol=0)
+        assert rel_fro(a, ora.layer_fwd("spatial", x, y, None, c6, w, sh.H, sh.dh)) > 1e-4
+        # block and step hand the option down
+        wb = {"spatial": wn, "temporal": wn}
+        c = ora.block_fwd(x, y, None, c6, wb, sh.H, sh.dh, rope_temporal=True)
+        d = ora.layer_fwd("temporal", ora.layer_fwd("spatial", x, y, None, c6, wn, sh.H, sh.dh), y, None, c6, wn, sh.H, sh.dh,
+                          rope_temporal=True)
+        np.testing.assert_allclose(c, d, atol=0)
+
+
 class TestPinsCatchMistakes:
     """Each case plants one plausible mistake in the oracle (on the CPU) and checks that
     at least one of the pins above fails."""
@@ -409,7 +502,8 @@ class TestPinsCatchMistakes:
     def _pins_fail(self, monkeypatch, name, wrong):
         monkeypatch.setattr(ora, name, wrong)
         failed = 0
-        suites = [TestBruteForce(), TestLibraryRoutines(), TestAttentionClosedForms(), TestLayerInvariants(), TestStep()]
+        suites = [TestBruteForce(), TestLibraryRoutines(), TestAttentionClosedForms(), TestLayerInvariants(), TestStep(),
+                  TestQkNormRotary()]
         for s in suites:
             for attr in dir(s):
                 if attr.startswith("test_"):
@@ -464,3 +558,31 @@ class TestPinsCatchMistakes:
     def test_spatial_temporal_swapped(self, monkeypatch):
         good_t = ora.temporal_attention
         assert self._pins_fail(monkeypatch, "spatial_attention", good_t) > 0
+
+    def test_rotary_turning_the_other_way(self, monkeypatch):
+        good = ora.rotary
+        assert self._pins_fail(monkeypatch, "rotary", lambda u, pos, theta=10000.0: good(u, -np.asarray(pos, dtype=np.float64), theta)) > 0
+
+    def test_rotary_pairing_first_half_with_second_half(self, monkeypatch):
+        def wrong(u, pos, theta=10000.0):
+            d = u.shape[-1]
+            w = theta ** (-2.0 * np.arange(d // 2) / d)
+            ang = np.asarray(pos, dtype=np.float64)[..., None] * w
+            a, b = u[..., :d // 2], u[..., d // 2:]
+            return np.concatenate([a * np.cos(ang) - b * np.sin(ang), b * np.cos(ang) + a * np.sin(ang)], -1)
+        assert self._pins_fail(monkeypatch, "rotary", wrong) > 0
+
+    def test_rotary_frequency_exponent_without_the_two(self, monkeypatch):
+        good = ora.rotary
+        assert self._pins_fail(monkeypatch, "rotary", lambda u, pos, theta=10000.0: good(u, pos, math.sqrt(theta))) > 0
+
+    def test_rms_norm_that_centres(self, monkeypatch):
+        def wrong(u, g, eps=1e-6):
+            c = u - u.mean(-1, keepdims=True)
+            return c / np.sqrt((c ** 2).mean(-1, keepdims=True) + eps) * g
+        assert self._pins_fail(monkeypatch, "rms_norm", wrong) > 0
+
+    def test_rms_norm_eps_outside_the_root(self, monkeypatch):
+        def wrong(u, g, eps=1e-6):
+            return u / (np.sqrt((u ** 2).mean(-1, keepdims=True)) + eps) * g
+        assert self._pins_fail(monkeypatch, "rms_norm", wrong) > 0
