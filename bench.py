@@ -161,6 +161,10 @@ def main():
     for i in range(sh.n_blocks):
         blocks.append({kind: {n: draw(s_, 0.02, torch.float32 if n == "ada_table" else torch.bfloat16)
                               for n, s_ in syn.layer_shapes(sh).items()} for kind in ("spatial", "temporal")})
+    for wb in blocks:   # scales of the optional q/k normalisation (read only by the variant timed after the step)
+        for lw_ in wb.values():
+            lw_["g_q"] = (1.0 + draw((sh.dh,), 0.2, torch.float32)).to(torch.bfloat16)
+            lw_["g_k"] = (1.0 + draw((sh.dh,), 0.2, torch.float32)).to(torch.bfloat16)
     x_in, y = draw((sh.B, sh.T, sh.S, sh.D), 1.0), draw((sh.B, sh.Ly, sh.D), 1.0)
     valid = [int(v) for v in syn.make_valid_len(sh, base, cfg["valid"])]
     tsteps = [float(t) for t in syn.make_timesteps(sh, base, cfg["t"])]
@@ -189,6 +193,25 @@ def main():
     fl = step_flops(sh, valid)
     step_tflops = fl["step"] / (ms_per_step * 1e-3) / 1e12
     print("[bench] step %.2f ms, %.1f TFLOP/s algorithmic" % (ms_per_step, step_tflops), file=sys.stderr, flush=True)
+
+    # the same step with per-head q/k normalisation and temporal rotary embedding switched on (the two
+    # options of the released model that the paper does not mention): reported beside the metric, not as it
+    variant_ms = None
+    if not args.only_stage and not args.no_stages:
+        shape_v = m.make_shape(sh.B, sh.T, sh.Hp, sh.Wp, sh.D, sh.H, sh.dh, sh.M, sh.Ly, sh.n_blocks,
+                               m.DDIT_FLAG_QK_NORM | m.DDIT_FLAG_ROPE_TEMPORAL)
+        ws_v = m.alloc_workspace(shape_v)
+        x_v = torch.empty_like(x_in)
+        step_v = lambda: m.ddit_denoise_step(shape_v, st, x_in, y, valid, tsteps, None, x_v, ws_v)
+        step_v()
+        torch.cuda.synchronize()
+        tv = time.perf_counter()
+        for _ in range(3):
+            step_v()
+        torch.cuda.synchronize()
+        variant_ms = (time.perf_counter() - tv) * 1e3 / 3
+        del ws_v, x_v
+        print("[bench] step with q/k normalisation + rotary embedding: %.2f ms" % variant_ms, file=sys.stderr, flush=True)
 
     # ---- per-kernel timings with HIP events on the stream the kernels run on
     def time_call(fn, reps):
@@ -245,6 +268,14 @@ def main():
             ms = time_call(lambda: m.ddit_modulated_layernorm_fwd(x32, lw["ada_table"], c6, 0, sh.L, 1e-6, xh), reps)
             gbs = 6.0 * N * D / (ms * 1e-3) / 1e9
             stages["modulated_layernorm"] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+        if want("qk_norm_rope"):
+            qk_buf = torch.randn(N, 3 * A, device="cuda").to(torch.bfloat16)
+            tab = torch.empty(sh.T * sh.dh, dtype=torch.float32, device="cuda")
+            ms = time_call(lambda: m.ddit_qk_norm_rope_fwd(qk_buf, 3 * A, N, sh.H, sh.dh, lw["g_q"], lw["g_k"], 1e-6, sh.S,
+                                                           sh.T, tab), reps)
+            gbs = 8.0 * N * A / (ms * 1e-3) / 1e9        # q and k read and written once, bf16
+            stages["qk_norm_rope"] = {"ms": round(ms, 4), "GBps": round(gbs, 1), "frac_hbm": round(gbs / PEAK_HBM_GBS, 4)}
+            del qk_buf
         # the layers around the step and the solver (latent with 4 channels, text width 4096)
         C_lat, C_text = 4, 4096
         io_w = {k: draw(s_, 0.02, torch.float32 if k == "final_table" else torch.bfloat16)
@@ -310,6 +341,7 @@ def main():
         "step_tflops": round(step_tflops, 1), "step_frac_mfma_peak": round(step_tflops / PEAK_BF16_TFLOPS, 4),
         "step_algorithmic_tflop": round(fl["step"] / 1e12, 2),
         "roofline": roofline, "stages": stages, "cpu_baseline": cpu,
+        "step_ms_with_qk_norm_and_rotary": None if variant_ms is None else round(variant_ms, 3),
         "paper_context": "paper reports only 'several seconds to tens of seconds' of DiT time per 30-step request on "
                          "H800 at 144p-360p (section 6.3); no per-step figure to compare with",
     }

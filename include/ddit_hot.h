@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-#define DDIT_ABI_VERSION 3u
+#define DDIT_ABI_VERSION 4u
 
 typedef enum {
   DDIT_OK = 0,
@@ -62,6 +62,16 @@ typedef enum { DDIT_ATTN_SPATIAL = 0, DDIT_ATTN_TEMPORAL = 1, DDIT_ATTN_CROSS = 
 /* flags of ddit_shape */
 #define DDIT_FLAG_TAPS 1u /* block/step: keep per-branch intermediates of the LAST layer pair run
                              (see ddit_tap_region) in the tail of the workspace, for tests */
+/* Two options of the self-attention that the paper's section 2.2 does not mention and the
+ * released model of its Table 1 has; both off by default.  They act on q and k between the
+ * q|k|v projection and the attention, in fp32, with one rounding to bf16: */
+#define DDIT_FLAG_QK_NORM 2u /* per-head RMS normalisation of the spatial and temporal self-attention's
+                                q and k:  u / sqrt(mean_d(u^2) + ln_eps) * g  over the dh elements of a
+                                head, g = the layer's g_q (queries) or g_k (keys).  Cross-attention is
+                                not normalised. */
+#define DDIT_FLAG_ROPE_TEMPORAL 4u /* rotary position embedding of the TEMPORAL self-attention's q and k
+                                (after the normalisation): the pair (u[2i], u[2i+1]) of every head is
+                                rotated by the angle t * 10000^(-2i/dh), t = the token's frame index */
 
 /* Problem shape.  Supported: dh in {64, 72}; D, A = H*dh, M, multiples of 8; A <= D
  * (A < D is one rank's share of a head-split sequence-parallel run); B <= 64. */
@@ -86,6 +96,7 @@ typedef struct {
   const void *w_fc1, *b_fc1; /* [M,D],  [M]  */
   const void *w_fc2, *b_fc2; /* [D,M],  [D]  */
   const float *ada_table;    /* [6,D] fp32 */
+  const void *g_q, *g_k;     /* [dh] bf16 each; read only with DDIT_FLAG_QK_NORM (else may be NULL) */
 } ddit_layer_weights;
 
 typedef struct {
@@ -114,7 +125,7 @@ int ddit_workspace_bytes(const ddit_shape *shape, size_t *bytes_out);
  * tap ids: */
 typedef enum {
   DDIT_TAP_XH_MSA = 0,      /* bf16 [N,D]  modulate(LN(x)) feeding QKV            */
-  DDIT_TAP_QKV = 1,         /* bf16 [N,3A] q | k | v                               */
+  DDIT_TAP_QKV = 1,         /* bf16 [N,3A] q | k | v as the attention reads them   */
   DDIT_TAP_O = 2,           /* bf16 [N,A]  self-attention output                   */
   DDIT_TAP_X_AFTER_ATTN = 3,  /* fp32 [N,D] stream after the gated attention add   */
   DDIT_TAP_QC = 4,          /* bf16 [N,A]  cross-attention queries                 */
@@ -194,6 +205,15 @@ typedef enum {
 int ddit_linear_fwd(int epilogue, const void *u, int64_t ld_u, const void *W, const void *bias, int64_t N,
                     int32_t n, int32_t k, void *out, int64_t ld_out, float *resid, const float *ada_table,
                     const float *c6, int gate_row, int64_t tokens_per_sample, void *hip_stream);
+
+/* In place on q | k, the first 2*H*dh columns of the rows of qk (bf16, row stride ld elements,
+ * N rows): per-head RMS normalisation with scales g_q, g_k (bf16 [dh]; both NULL = none) and,
+ * if rope_table_or_null is given, rotary embedding with frame index t = (row / S) % T
+ * (DDIT_FLAG_QK_NORM / DDIT_FLAG_ROPE_TEMPORAL above).  rope_table_or_null: device scratch of
+ * T*dh floats that the call fills with the (cos, sin) table first; NULL = no rotation. */
+int ddit_qk_norm_rope_fwd(void *qk, int64_t ld, int64_t N, int32_t H, int32_t dh, const void *g_q,
+                          const void *g_k, float eps, int64_t S, int32_t T, float *rope_table_or_null,
+                          void *hip_stream);
 
 /* ---- output tiles of the linear: for tuning and for parity tests of every compiled tile ----
  * The linear is compiled for a short list of output tiles (rows x cols of out per workgroup) and

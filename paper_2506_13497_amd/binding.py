@@ -19,7 +19,7 @@ DDIT_OK = 0
 DDIT_ERR_INVALID_ARG, DDIT_ERR_UNSUPPORTED, DDIT_ERR_WORKSPACE, DDIT_ERR_ALIGNMENT, DDIT_ERR_HIP = -1, -2, -3, -4, -5
 DDIT_ATTN_SPATIAL, DDIT_ATTN_TEMPORAL, DDIT_ATTN_CROSS = 0, 1, 2
 DDIT_EPI_BF16, DDIT_EPI_GELU_BF16, DDIT_EPI_RESIDUAL_F32 = 0, 1, 2
-DDIT_FLAG_TAPS = 1
+DDIT_FLAG_TAPS, DDIT_FLAG_QK_NORM, DDIT_FLAG_ROPE_TEMPORAL = 1, 2, 4
 TAP_NAMES = ["xh_msa", "qkv", "o", "x_after_attn", "qc", "kvc", "oc", "x_after_cross", "xh_mlp", "h", "x_out"]
 _TAP_DTYPE = {"x_after_attn": torch.float32, "x_after_cross": torch.float32, "x_out": torch.float32}
 
@@ -28,7 +28,7 @@ EXPORTS = ["ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_wo
            "ddit_linear_fwd", "ddit_timestep_conditioning", "ddit_io_workspace_bytes", "ddit_embed_latent",
            "ddit_embed_caption", "ddit_output_head", "ddit_eps_theta", "ddit_solver_step", "ddit_sample",
            "ddit_cross_kv_bytes", "ddit_cross_kv_precompute", "ddit_denoise_step_cached", "ddit_linear_tile_count",
-           "ddit_linear_tile_info", "ddit_linear_tile_choice", "ddit_linear_fwd_tile"]
+           "ddit_linear_tile_info", "ddit_linear_tile_choice", "ddit_linear_fwd_tile", "ddit_qk_norm_rope_fwd"]
 
 
 class ddit_shape(C.Structure):
@@ -39,7 +39,7 @@ class ddit_shape(C.Structure):
 
 
 _LAYER_FIELDS = ["w_qkv", "b_qkv", "w_o", "b_o", "w_cq", "b_cq", "w_ckv", "b_ckv", "w_co", "b_co",
-                 "w_fc1", "b_fc1", "w_fc2", "b_fc2", "ada_table"]
+                 "w_fc1", "b_fc1", "w_fc2", "b_fc2", "ada_table", "g_q", "g_k"]
 
 
 class ddit_layer_weights(C.Structure):
@@ -94,6 +94,8 @@ def _load() -> C.CDLL:
     lib.ddit_linear_fwd.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
                                     C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                     C.c_int64, C.c_void_p]
+    lib.ddit_qk_norm_rope_fwd.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                          C.c_float, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
     lib.ddit_linear_fwd_tile.argtypes = [C.c_int] + list(lib.ddit_linear_fwd.argtypes)
     lib.ddit_linear_tile_count.argtypes = []
     lib.ddit_linear_tile_info.argtypes = [C.c_int] + [C.POINTER(C.c_int32)] * 4
@@ -228,6 +230,11 @@ def ddit_linear_fwd(epilogue: int, u, ld_u: int, W, bias, N: int, n: int, k: int
                     ada_table=None, c6=None, gate_row: int = -1, tokens_per_sample: int = 1) -> None:
     _check(_lib.ddit_linear_fwd(epilogue, _ptr(u), ld_u, _ptr(W), _ptr(bias), N, n, k, _ptr(out), ld_out,
                                 _ptr(resid), _ptr(ada_table), _ptr(c6), gate_row, tokens_per_sample, _stream()))
+
+
+def ddit_qk_norm_rope_fwd(qk, ld: int, N: int, H: int, dh: int, g_q, g_k, eps: float, S: int, T: int,
+                          rope_table=None) -> None:
+    _check(_lib.ddit_qk_norm_rope_fwd(_ptr(qk), ld, N, H, dh, _ptr(g_q), _ptr(g_k), eps, S, T, _ptr(rope_table), _stream()))
 
 
 def ddit_linear_tile_count() -> int:

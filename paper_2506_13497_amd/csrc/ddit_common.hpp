@@ -76,6 +76,12 @@ int temporal_attn_max_T();   // longest sequence the dedicated temporal kernel t
 int launch_temporal_attn(const void *q, const void *k, const void *v, void *o, float *lse, int64_t ld_q,
                          int64_t ld_kv, int64_t ld_o, int B, int T, int S, int H, int dh, hipStream_t s);
 
+// per-head RMS normalisation and rotary embedding of q | k, in place (qk_norm_rope.hip).
+// g_q/g_k null: no normalisation; rope_table null: no rotation
+int launch_rope_table(float *table, int T, int dh, hipStream_t s);   // [T, dh/2] (cos, sin)
+int launch_qk_norm_rope(void *qk, int64_t ld, int64_t N, int H, int dh, const void *g_q, const void *g_k, float eps,
+                        const float *rope_table, int64_t S, int T, hipStream_t s);
+
 int launch_cast_bf16_to_f32(const void *in, float *out, int64_t n, hipStream_t s);
 int launch_cast_f32_to_bf16(const float *in, void *out, int64_t n, hipStream_t s);
 struct CondArgs {

@@ -36,7 +36,7 @@ struct Dims {
 };
 
 struct Layout {
-  size_t x, xh, qkv, o, kvc, h, c6, cond, taps, total;
+  size_t x, xh, qkv, o, kvc, h, c6, cond, rope, taps, total;
   size_t tap_off[2][DDIT_TAP_COUNT], tap_bytes[DDIT_TAP_COUNT];
 };
 
@@ -76,6 +76,7 @@ void make_layout(const Dims &d, uint32_t flags, Layout *lo) {
   lo->h = take((size_t)d.N * d.M * 2);
   lo->c6 = take((size_t)d.B * 6 * d.D * 4);
   lo->cond = take((size_t)d.B * (256 + 2 * d.D) * 4);
+  lo->rope = (flags & DDIT_FLAG_ROPE_TEMPORAL) ? take((size_t)d.T * d.dh * 4) : 0;
   lo->taps = off;
   const size_t ND = (size_t)d.N * d.D, NA = (size_t)d.N * d.A;
   const size_t tb[DDIT_TAP_COUNT] = {ND * 2, 3 * NA * 2, NA * 2, ND * 4, NA * 2, (size_t)d.B * d.Ly * 2 * d.A * 2,
@@ -98,7 +99,11 @@ int check_valid_len(const int32_t *vl, const Dims &d) {
   return DDIT_OK;
 }
 
-int check_layer_weights(const ddit_layer_weights &w, const char *which) {
+int check_layer_weights(const ddit_layer_weights &w, const char *which, uint32_t flags) {
+  if (flags & DDIT_FLAG_QK_NORM) {
+    if (!w.g_q || !w.g_k) { set_error("%s: DDIT_FLAG_QK_NORM needs g_q and g_k", which); return DDIT_ERR_INVALID_ARG; }
+    if (!aligned16(w.g_q) || !aligned16(w.g_k)) { set_error("%s: g_q / g_k not 16-byte aligned", which); return DDIT_ERR_ALIGNMENT; }
+  }
   const void *req[] = {w.w_qkv, w.w_o, w.w_cq, w.w_ckv, w.w_co, w.w_fc1, w.w_fc2, w.ada_table};
   const char *names[] = {"w_qkv", "w_o", "w_cq", "w_ckv", "w_co", "w_fc1", "w_fc2", "ada_table"};
   for (int i = 0; i < 8; ++i)
@@ -166,8 +171,8 @@ struct Taps {
 // One layer on the fp32 stream x (in the workspace).
 // kvc_cached: this layer's cross-attention k|v [B*Ly, 2A] formed earlier, or null (then y is projected here)
 int run_layer(ddit_attn_kind kind, const Dims &d, const ddit_layer_weights &w, const void *y, const void *kvc_cached,
-              const int32_t *valid_len, const float *c6, float eps, unsigned char *ws, const Layout &lo,
-              const Taps &tp, hipStream_t s) {
+              const int32_t *valid_len, const float *c6, float eps, uint32_t flags, unsigned char *ws,
+              const Layout &lo, const Taps &tp, hipStream_t s) {
   float *x = reinterpret_cast<float *>(ws + lo.x);
   void *xh = ws + lo.xh;
   unsigned char *qkv = ws + lo.qkv;
@@ -191,6 +196,13 @@ int run_layer(ddit_attn_kind kind, const Dims &d, const ddit_layer_weights &w, c
   DDIT_TRY(tp.keep(DDIT_TAP_XH_MSA, xh));
   base(xh, D, w.w_qkv, w.b_qkv, N, (int)(3 * A), (int)D); g.out = qkv; g.ld_out = 3 * A;
   DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
+  {
+    const bool norm = (flags & DDIT_FLAG_QK_NORM) != 0;
+    const bool rope = (flags & DDIT_FLAG_ROPE_TEMPORAL) != 0 && kind == DDIT_ATTN_TEMPORAL;
+    if (norm || rope)
+      DDIT_TRY(launch_qk_norm_rope(qkv, 3 * A, N, (int)d.H, (int)d.dh, norm ? w.g_q : nullptr, norm ? w.g_k : nullptr, eps,
+                                   rope ? reinterpret_cast<const float *>(ws + lo.rope) : nullptr, d.S, (int)d.T, s));
+  }
   DDIT_TRY(tp.keep(DDIT_TAP_QKV, qkv));
   DDIT_TRY(run_attention(kind, d, qkv, qkv + A * 2, qkv + 2 * A * 2, 3 * A, 3 * A, nullptr, o, A, nullptr, s));
   DDIT_TRY(tp.keep(DDIT_TAP_O, o));
@@ -374,16 +386,18 @@ int ddit_stdit_block_fwd(const ddit_shape *shape, const ddit_block_weights *weig
   if (!aligned16(c6)) { set_error("c6 must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT; }
   DDIT_TRY(check_common(d, lo, x_in, y, x_out, workspace, workspace_bytes));
   DDIT_TRY(check_valid_len(y_valid_len_host, d));
-  DDIT_TRY(check_layer_weights(weights->spatial, "spatial"));
-  DDIT_TRY(check_layer_weights(weights->temporal, "temporal"));
+  DDIT_TRY(check_layer_weights(weights->spatial, "spatial", shape->flags));
+  DDIT_TRY(check_layer_weights(weights->temporal, "temporal", shape->flags));
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
   float *x = reinterpret_cast<float *>(ws + lo.x);
   Taps tp{(shape->flags & DDIT_FLAG_TAPS) != 0, ws, &lo, 0, s};
   DDIT_TRY(launch_cast_bf16_to_f32(x_in, x, d.N * d.D, s));
-  DDIT_TRY(run_layer(DDIT_ATTN_SPATIAL, d, weights->spatial, y, nullptr, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+  if (shape->flags & DDIT_FLAG_ROPE_TEMPORAL)
+    DDIT_TRY(launch_rope_table(reinterpret_cast<float *>(ws + lo.rope), (int)d.T, (int)d.dh, s));
+  DDIT_TRY(run_layer(DDIT_ATTN_SPATIAL, d, weights->spatial, y, nullptr, y_valid_len_host, c6, shape->ln_eps, shape->flags, ws, lo, tp, s));
   tp.layer = 1;
-  DDIT_TRY(run_layer(DDIT_ATTN_TEMPORAL, d, weights->temporal, y, nullptr, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+  DDIT_TRY(run_layer(DDIT_ATTN_TEMPORAL, d, weights->temporal, y, nullptr, y_valid_len_host, c6, shape->ln_eps, shape->flags, ws, lo, tp, s));
   return launch_cast_f32_to_bf16(x, x_out, d.N * d.D, s);
 }
 
@@ -473,8 +487,8 @@ int ddit_denoise_step_cached(const ddit_shape *shape, const ddit_step_weights *w
   DDIT_TRY(check_common(d, lo, x_in, y, x_out, workspace, workspace_bytes));
   DDIT_TRY(check_valid_len(y_valid_len_host, d));
   for (int i = 0; i < shape->n_blocks; ++i) {
-    DDIT_TRY(check_layer_weights(weights->blocks[i].spatial, "spatial"));
-    DDIT_TRY(check_layer_weights(weights->blocks[i].temporal, "temporal"));
+    DDIT_TRY(check_layer_weights(weights->blocks[i].spatial, "spatial", shape->flags));
+    DDIT_TRY(check_layer_weights(weights->blocks[i].temporal, "temporal", shape->flags));
   }
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   unsigned char *ws = reinterpret_cast<unsigned char *>(workspace);
@@ -484,15 +498,17 @@ int ddit_denoise_step_cached(const ddit_shape *shape, const ddit_step_weights *w
                                       reinterpret_cast<float *>(ws + lo.cond), hip_stream));
   Taps tp{(shape->flags & DDIT_FLAG_TAPS) != 0, ws, &lo, 0, s};
   DDIT_TRY(launch_cast_bf16_to_f32(x_in, x, d.N * d.D, s));
+  if (shape->flags & DDIT_FLAG_ROPE_TEMPORAL)
+    DDIT_TRY(launch_rope_table(reinterpret_cast<float *>(ws + lo.rope), (int)d.T, (int)d.dh, s));
   const size_t kv_layer = (size_t)d.B * d.Ly * 2 * d.A * 2;
   const unsigned char *kv = reinterpret_cast<const unsigned char *>(cross_kv_or_null);
   for (int i = 0; i < shape->n_blocks; ++i) {
     tp.layer = 0;
     DDIT_TRY(run_layer(DDIT_ATTN_SPATIAL, d, weights->blocks[i].spatial, y, kv ? kv + (size_t)(2 * i) * kv_layer : nullptr,
-                       y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+                       y_valid_len_host, c6, shape->ln_eps, shape->flags, ws, lo, tp, s));
     tp.layer = 1;
     DDIT_TRY(run_layer(DDIT_ATTN_TEMPORAL, d, weights->blocks[i].temporal, y,
-                       kv ? kv + (size_t)(2 * i + 1) * kv_layer : nullptr, y_valid_len_host, c6, shape->ln_eps, ws, lo, tp, s));
+                       kv ? kv + (size_t)(2 * i + 1) * kv_layer : nullptr, y_valid_len_host, c6, shape->ln_eps, shape->flags, ws, lo, tp, s));
   }
   return launch_cast_f32_to_bf16(x, x_out, d.N * d.D, s);
 }
@@ -512,6 +528,24 @@ int ddit_modulated_layernorm_fwd(const float *x, const float *ada_table, const f
   }
   return launch_modulated_layernorm(x, ada_table, c6, which, N, tokens_per_sample, D, eps, out,
                                     reinterpret_cast<hipStream_t>(hip_stream));
+}
+
+int ddit_qk_norm_rope_fwd(void *qk, int64_t ld, int64_t N, int32_t H, int32_t dh, const void *g_q, const void *g_k,
+                          float eps, int64_t S, int32_t T, float *rope_table_or_null, void *hip_stream) {
+  if (!qk) { set_error("qk must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if (N < 0 || H < 1 || S < 1 || T < 1 || !(eps > 0.f)) {
+    set_error("qk_norm_rope: N=%lld H=%d S=%lld T=%d eps=%g", (long long)N, H, (long long)S, T, (double)eps);
+    return DDIT_ERR_INVALID_ARG;
+  }
+  if (dh != 64 && dh != 72) { set_error("dh=%d: supported head dims are 64 and 72", dh); return DDIT_ERR_UNSUPPORTED; }
+  if ((g_q == nullptr) != (g_k == nullptr)) { set_error("g_q and g_k must be given together"); return DDIT_ERR_INVALID_ARG; }
+  if (ld < 2 * (int64_t)H * dh || ld % 8) { set_error("ld=%lld invalid for 2*H*dh=%lld", (long long)ld, 2LL * H * dh); return DDIT_ERR_INVALID_ARG; }
+  if (!aligned16(qk) || (g_q && (!aligned16(g_q) || !aligned16(g_k))) || (rope_table_or_null && !aligned16(rope_table_or_null))) {
+    set_error("pointers must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT;
+  }
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  if (rope_table_or_null) DDIT_TRY(launch_rope_table(rope_table_or_null, T, dh, s));
+  return launch_qk_norm_rope(qk, ld, N, H, dh, g_q, g_k, eps, rope_table_or_null, S, T, s);
 }
 
 int ddit_linear_tile_count(void) { return gemm_tile_count(); }

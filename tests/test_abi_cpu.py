@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol(m):
     for n in names:
         assert hasattr(lib, n), "missing export " + n
     assert sorted(m.binding.EXPORTS) == names
-    assert m.ddit_abi_version() == 3
+    assert m.ddit_abi_version() == 4
 
 
 def test_status_strings(m):
@@ -154,6 +154,28 @@ def test_linear_and_layernorm_validation(m):
     assert lib.ddit_modulated_layernorm_fwd(P(0x1000), P(0x2000), P(0x3000), 2, 4, 4, 64, 1e-6, P(0x4000), None) == -1  # which
     assert lib.ddit_modulated_layernorm_fwd(P(0x1000), P(0x2000), P(0x3000), 0, 4, 4, 60, 1e-6, P(0x4000), None) == -2  # D % 8
     assert lib.ddit_modulated_layernorm_fwd(None, P(0x2000), P(0x3000), 0, 4, 4, 64, 1e-6, P(0x4000), None) == -1
+
+
+def test_qk_norm_rope_validation_and_workspace(m):
+    lib = m.binding._lib
+    P = C.c_void_p
+    ok = (P(0x1000), 3 * 144, 10, 2, 72, P(0x2000), P(0x3000), 1e-6, 5, 2, None, None)
+    def call(**kw):
+        names = ("qk", "ld", "N", "H", "dh", "g_q", "g_k", "eps", "S", "T", "tab", "stream")
+        a = dict(zip(names, ok)); a.update(kw)
+        return lib.ddit_qk_norm_rope_fwd(*[a[n] for n in names])
+    assert call(qk=None) == -1
+    assert call(dh=80) == -2
+    assert call(ld=280) == -1                    # narrower than q | k
+    assert call(g_k=None) == -1                  # scales come in pairs
+    assert call(eps=0.0) == -1
+    assert call(qk=P(0x1004)) == -4
+    assert call(tab=P(0x4004)) == -4
+    assert call(T=0) == -1
+    # the rotary table lives in the workspace only when asked for
+    plain = m.ddit_workspace_bytes(_shape(m))
+    assert m.ddit_workspace_bytes(_shape(m, flags=m.DDIT_FLAG_ROPE_TEMPORAL)) > plain
+    assert m.ddit_workspace_bytes(_shape(m, flags=m.DDIT_FLAG_QK_NORM)) == plain
 
 
 def test_linear_tile_list_and_cost_model(m):

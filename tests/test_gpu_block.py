@@ -48,13 +48,15 @@ def _run_block(lib, sh, wb, act, c6, valid, flags=0):
     return shape, ws, x_out
 
 
-def _check_block_with_taps(lib, sh, base, table_std, valid):
-    wb = syn.make_block_weights(sh, base, 0, table_std=table_std)
+def _check_block_with_taps(lib, sh, base, table_std, valid, qk_norm=False, rope=False):
+    wb = syn.make_block_weights(sh, base, 0, qk_norm=qk_norm, table_std=table_std)
     act = syn.make_activations(sh, base)
     c6 = syn.make_c6(sh, base, std=0.5)
-    shape, ws, x_out = _run_block(lib, sh, wb, act, c6, valid, flags=lib.DDIT_FLAG_TAPS)
+    flags = lib.DDIT_FLAG_TAPS | (lib.DDIT_FLAG_QK_NORM if qk_norm else 0) | (lib.DDIT_FLAG_ROPE_TEMPORAL if rope else 0)
+    shape, ws, x_out = _run_block(lib, sh, wb, act, c6, valid, flags=flags)
     taps = {}
-    ref = ora.block_fwd(to_f64(act["x"]), to_f64(act["y"]), valid, c6.astype(np.float64), dict_f64(wb), sh.H, sh.dh, taps)
+    ref = ora.block_fwd(to_f64(act["x"]), to_f64(act["y"]), valid, c6.astype(np.float64), dict_f64(wb), sh.H, sh.dh, taps,
+                        rope_temporal=rope)
     assert_parity(dev_to_f64(x_out), ref, "block output")
     N, D, A, M = sh.N, sh.D, sh.A, sh.M
     for layer, kind in enumerate(("spatial", "temporal")):
@@ -95,8 +97,8 @@ def _oracle_layer_out(monkeypatch):
     """Record each layer's output stream in the oracle's taps (test-side wrapper, oracle untouched)."""
     orig = ora.layer_fwd
 
-    def wrapped(kind, x, y, valid_len, c6, w, H, dh, taps=None):
-        out = orig(kind, x, y, valid_len, c6, w, H, dh, taps)
+    def wrapped(kind, x, y, valid_len, c6, w, H, dh, taps=None, **kw):
+        out = orig(kind, x, y, valid_len, c6, w, H, dh, taps, **kw)
         if taps is not None:
             taps["x_layer_out"] = out.copy()
         return out
@@ -122,6 +124,27 @@ def test_block_narrow_attention_width(lib):
     """4 of 16 heads (A=288 < D=1152): one rank's share of a head-split run."""
     sh = syn.Shape(1, 4, 6, 9, 1152, 4, 72, 4608, 300, 1)
     _check_block_with_taps(lib, sh, 22, 0.02, [77])
+
+
+@pytest.mark.parametrize("qk_norm,rope", [(True, False), (False, True), (True, True)], ids=["qknorm", "rope", "qknorm+rope"])
+def test_block_c1_qk_norm_and_rotary(lib, qk_norm, rope):
+    """The two optional pieces of the self-attention, stage by stage: the q | k tap holds what the
+    attention reads (normalised, and rotated in the temporal layer)."""
+    _check_block_with_taps(lib, C1, 1, 0.02, None, qk_norm=qk_norm, rope=rope)
+
+
+def test_block_ragged_batch2_masked_qk_norm_and_rotary(lib):
+    sh = syn.Shape(2, 3, 5, 7, 1152, 16, 72, 4608, 300, 1)
+    _check_block_with_taps(lib, sh, 23, 0.02, [45, 300], qk_norm=True, rope=True)
+
+
+def test_qk_norm_flag_needs_scales(lib):
+    sh = C1
+    wb = syn.make_block_weights(sh, 1, 0)            # no g_q / g_k
+    act = syn.make_activations(sh, 1)
+    with pytest.raises(lib.DditError) as e:
+        _run_block(lib, sh, wb, act, syn.make_c6(sh, 1, 0.5), None, flags=lib.DDIT_FLAG_QK_NORM)
+    assert e.value.status == lib.DDIT_ERR_INVALID_ARG
 
 
 def test_block_in_place_and_deterministic(lib):
@@ -216,6 +239,25 @@ def test_step_c1_given_temb(lib):
     ref = ora.denoise_step(to_f64(act["x"]), to_f64(act["y"]), None, None, dict_f64(sw), [dict_f64(b) for b in blocks],
                            sh.H, sh.dh, temb=temb.astype(np.float64))
     assert_parity(dev_to_f64(x_out), ref, "C1 step")
+
+
+def test_step_two_blocks_qk_norm_and_rotary(lib):
+    """Both options through the whole step (two blocks, batch 2, masked text, head dim 64)."""
+    sh = syn.Shape(2, 5, 5, 7, 256, 4, 64, 1024, 24, 2)
+    sw = syn.make_step_weights(sh, 33, w_std=0.05)
+    blocks = [syn.make_block_weights(sh, 33, i, qk_norm=True, table_std=0.5) for i in range(2)]
+    act = syn.make_activations(sh, 33)
+    t = [250.0, 40.0]
+    valid = [11, 24]
+    flags = lib.DDIT_FLAG_QK_NORM | lib.DDIT_FLAG_ROPE_TEMPORAL
+    _, _, x_out = _run_step(lib, sh, sw, blocks, act, valid, t=t, flags=flags)
+    ref = ora.denoise_step(to_f64(act["x"]), to_f64(act["y"]), valid, np.array(t), dict_f64(sw),
+                           [dict_f64(b) for b in blocks], sh.H, sh.dh, rope_temporal=True)
+    assert_parity(dev_to_f64(x_out), ref, "2-block step with q/k normalisation and rotary embedding")
+    plain = ora.denoise_step(to_f64(act["x"]), to_f64(act["y"]), valid, np.array(t), dict_f64(sw),
+                             [{k: {n: v for n, v in w.items() if n not in ("g_q", "g_k")} for k, w in dict_f64(b).items()}
+                              for b in blocks], sh.H, sh.dh)
+    assert rel_fro(ref, plain) > 1e-3, "the options must change the result for the comparison to mean anything"
 
 
 def test_step_two_blocks_batch2_timesteps_stress(lib):

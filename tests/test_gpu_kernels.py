@@ -49,6 +49,72 @@ def test_modulated_layernorm(lib, N, tps, D):
         assert_parity(dev_to_f64(out), ref, "modulated LN which=%d" % which)
 
 
+# ----------------------------------------------------------------------------- q/k normalisation, rotary embedding
+@pytest.mark.parametrize("N,H,dh,S,T,extra", [(37, 16, 72, 5, 3, 0), (1000, 4, 72, 7, 30, 16), (130, 2, 64, 1, 130, 8),
+                                              (3 * 40 * 11, 16, 72, 11, 40, 0), (1, 1, 64, 1, 1, 0)])
+@pytest.mark.parametrize("norm,rope", [(True, False), (False, True), (True, True)], ids=["norm", "rope", "norm+rope"])
+def test_qk_norm_rope(lib, N, H, dh, S, T, extra, norm, rope):
+    """In place on the q | k columns of a fused q|k|v buffer; v and any padding columns stay bit for bit."""
+    A = H * dh
+    ld = 3 * A + extra
+    buf = syn.normal_bits((31, N, H, dh), (N, ld), 1.5)
+    gq = syn.f32_to_bf16_bits((1 + 0.2 * np.random.default_rng(1).standard_normal(dh)).astype(np.float32))
+    gk = syn.f32_to_bf16_bits((1 + 0.2 * np.random.default_rng(2).standard_normal(dh)).astype(np.float32))
+    d = to_dev(buf)
+    tab = torch.empty(T * dh, dtype=torch.float32, device="cuda") if rope else None
+    lib.ddit_qk_norm_rope_fwd(d, ld, N, H, dh, to_dev(gq) if norm else None, to_dev(gk) if norm else None, 1e-6, S, T, tab)
+    torch.cuda.synchronize()
+    got = dev_to_f64(d)
+    x = to_f64(buf)
+    frame = ((np.arange(N) // S) % T).astype(np.float64)[:, None]
+    for i, g in enumerate((gq, gk)):
+        u = x[:, i * A:(i + 1) * A].reshape(N, H, dh)
+        if norm:
+            u = ora.rms_norm(u, to_f64(g), 1e-6)
+        if rope:
+            u = ora.rotary(u, frame)
+        assert_parity(got[:, i * A:(i + 1) * A], u.reshape(N, A), "q/k part %d" % i)
+    assert np.array_equal(got[:, 2 * A:], x[:, 2 * A:]), "v or padding columns were touched"
+    if rope:   # the table the call leaves behind: (cos, sin) of t * 10000^(-2i/dh)
+        tt = dev_to_f64(tab).reshape(T, dh // 2, 2)
+        ang = np.arange(T)[:, None] * 10000.0 ** (-2.0 * np.arange(dh // 2) / dh)
+        assert np.abs(tt[..., 0] - np.cos(ang)).max() < 2e-5 and np.abs(tt[..., 1] - np.sin(ang)).max() < 2e-5
+
+
+def test_qk_norm_rope_480p_shape_sampled_rows(lib):
+    """The benchmark's shape (48600 tokens, 16 x 72, 30 frames of 1620): sampled token rows against the oracle."""
+    N, H, dh, S, T = 48600, 16, 72, 1620, 30
+    A = H * dh
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    d = (torch.randn(N, 3 * A, generator=g, device="cuda") * 1.5).to(torch.bfloat16)
+    before = d.clone()
+    gq = syn.f32_to_bf16_bits((1 + 0.2 * np.random.default_rng(3).standard_normal(dh)).astype(np.float32))
+    gk = syn.f32_to_bf16_bits((1 + 0.2 * np.random.default_rng(4).standard_normal(dh)).astype(np.float32))
+    tab = torch.empty(T * dh, dtype=torch.float32, device="cuda")
+    lib.ddit_qk_norm_rope_fwd(d, 3 * A, N, H, dh, to_dev(gq), to_dev(gk), 1e-6, S, T, tab)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, 1, S - 1, S, N - S - 1, N - 1], np.random.default_rng(6).integers(0, N, 500)]))
+    ridx = torch.from_numpy(rows).cuda()
+    got, x = dev_to_f64(d[ridx]), dev_to_f64(before[ridx])
+    frame = ((rows // S) % T).astype(np.float64)[:, None]
+    for i, gg in enumerate((gq, gk)):
+        u = ora.rotary(ora.rms_norm(x[:, i * A:(i + 1) * A].reshape(-1, H, dh), to_f64(gg), 1e-6), frame)
+        assert_parity(got[:, i * A:(i + 1) * A], u.reshape(-1, A), "q/k part %d, sampled rows" % i)
+    assert torch.equal(d[:, 2 * A:], before[:, 2 * A:])
+
+
+def test_qk_norm_rope_empty_and_identity(lib):
+    buf = syn.normal_bits((32,), (64, 3 * 144), 1.0)
+    d = to_dev(buf)
+    lib.ddit_qk_norm_rope_fwd(d, 3 * 144, 0, 2, 72, None, None, 1e-6, 4, 4, None)      # no rows
+    lib.ddit_qk_norm_rope_fwd(d, 3 * 144, 64, 2, 72, None, None, 1e-6, 4, 4, None)     # neither option: nothing to do
+    # T = 1: every token is in frame 0, the rotation is the identity
+    tab = torch.empty(72, dtype=torch.float32, device="cuda")
+    lib.ddit_qk_norm_rope_fwd(d, 3 * 144, 64, 2, 72, None, None, 1e-6, 64, 1, tab)
+    torch.cuda.synchronize()
+    assert torch.equal(d, to_dev(buf))
+
+
 # ----------------------------------------------------------------------------- linear + epilogues
 LIN_CASES = [
     # N, n, k
