@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-#define DDIT_ABI_VERSION 4u
+#define DDIT_ABI_VERSION 5u
 
 typedef enum {
   DDIT_OK = 0,
@@ -319,6 +319,82 @@ int ddit_sample(const ddit_shape *shape, const ddit_step_weights *weights, const
                 const void *cross_kv_or_null, const void *cross_kv_uncond_or_null, float guidance,
                 int32_t n_steps, int32_t first_step, int32_t last_step, float *eps_scratch, void *workspace,
                 size_t workspace_bytes, void *hip_stream);
+
+/* ---- what the paper builds on top of the step: choosing and changing a request's GPUs ----
+ * Host only (no GPU, no HIP call, host pointers throughout): the optimal degree of parallelism
+ * from a table of measured step times (section 4.2.3), a buddy allocator of GPUs (section 5) and
+ * the greedy step-granular scheduler (section 4.2.3 and the scheduling algorithm of the appendix)
+ * run as an event simulation over such a table.  All times are integer microseconds, so results
+ * are exact.  bench.py --dop-table measures the table for this library on one MI355X. */
+
+/* B for one resolution: step_us_row_host[k] = time of one step on 2^k GPUs, k < n_dop.
+ * z(2^k) = 1 - t_k / t_{k-1} (the paper's change rate); B = the parallel size with the largest z
+ * (the smaller size on ties), or 1 if no z exceeds z_min = z_min_num / z_min_den (the paper
+ * reports B = 1 for its lowest resolution; with 0/1 that is "no doubling gains anything").
+ * Exact integer comparisons.  Step times in [1, 2^40]. */
+int ddit_optimal_dop(const int64_t *step_us_row_host, int32_t n_dop, int64_t z_min_num, int64_t z_min_den,
+                     int32_t *dop_out);
+
+/* Buddy system over GPUs 0 .. n_gpus-1 (a power of two, at most 4096): blocks are aligned runs of
+ * 2^k GPUs.  alloc takes the SMALLEST free block that is large enough, the lowest-numbered of
+ * that size, and splits it keeping the lower half each time; *start_out = -1 when nothing fits
+ * (that is not an error).  release merges a block with its buddy as long as the buddy is free;
+ * it refuses a range that is not an aligned block or not allocated as a whole.  The pool is host
+ * memory owned by the library between create and destroy; calls on one pool must not overlap. */
+int ddit_buddy_create(int32_t n_gpus, void **pool_out);
+int ddit_buddy_alloc(void *pool, int32_t size, int32_t *start_out);
+int ddit_buddy_release(void *pool, int32_t start, int32_t size);
+int ddit_buddy_free_gpus(void *pool, int32_t *free_out);
+int ddit_buddy_destroy(void *pool);
+
+typedef struct {
+  uint32_t struct_size;   /* sizeof(ddit_sched_config) */
+  int32_t n_gpus;         /* power of two, at most 4096 */
+  int32_t n_steps;        /* denoising steps per request (30 in the paper's evaluation) */
+  int32_t n_resolutions;  /* R */
+  int32_t n_dop;          /* parallel sizes in the table: 1, 2, ..., 2^(n_dop-1) <= n_gpus */
+  int32_t vae_gpus;       /* GPUs a request keeps for the decoder (power of two) */
+  const int64_t *step_us; /* HOST [R, n_dop]: DiT_step_time(parallel size, resolution), each in [1, 2^40] */
+  const int32_t *opt_dop; /* HOST [R]: B(r), a power of two inside the table */
+  const int64_t *vae_us;  /* HOST [R] or NULL: time of the decoder phase; 0 = none */
+} ddit_sched_config;
+
+typedef struct { int64_t arrival_us; int32_t resolution; int32_t reserved; } ddit_sched_request;
+
+typedef struct {
+  int64_t start_us, dit_end_us, end_us; /* first step starts / last step ends / GPUs all given back */
+  int64_t starvation;                   /* the priority value when last brought up to date */
+  int32_t first_dop, final_dop;         /* GPUs at the start / during the last step */
+  int32_t promotions, reserved;         /* scheduling passes that gave the request more GPUs */
+} ddit_sched_record;
+
+typedef enum { DDIT_SCHED_START = 0, DDIT_SCHED_PROMOTE = 1, DDIT_SCHED_DIT_DONE = 2, DDIT_SCHED_RELEASE = 3 } ddit_sched_event_kind;
+typedef struct { int64_t time_us; int32_t kind, request, gpu_start, gpu_count; } ddit_sched_event;
+typedef struct { int64_t occupancy_gpu_us, makespan_us; } ddit_sched_totals;
+
+/* Serves requests_host[0 .. n_requests-1] (ordered by arrival) and reports what happened.
+ * Rules (the first four are the paper's, the rest are this library's readings of what it leaves open):
+ *  - first come, first served; a waiting request asks for B(r) GPUs and goes down (B, B/2, .., 1)
+ *    until the allocator has a block; below B it is "hungry";
+ *  - whenever GPUs were released, every hungry request's starvation grows by
+ *    (steps done since its last update) x (its step time now - its step time at B), and hungry
+ *    requests are promoted in descending order of starvation, before the waiting queue is served;
+ *  - a promotion takes effect between two denoising steps: the step in flight ends at the old
+ *    rate, later steps run at the new one; the new GPUs count as occupied from the grant;
+ *  - after the last step the request keeps the vae_gpus lowest-numbered GPUs of its
+ *    lowest-numbered block (at most that block) for vae_us[r], and gives back the rest at once;
+ *  - a promotion from p to 2p GPUs takes ANY free block of p GPUs from the allocator, and repeats
+ *    until B or until none is free; a request thus holds a list of blocks;
+ *  - within one microsecond: step ends and decoder ends (by request index), then arrivals, then one
+ *    scheduling pass; equal starvation goes to the earlier request;
+ *  - blocks are given back in the order they were granted (the decoder's block: upper halves first).
+ * records_out: n_requests entries.  events_out_or_null: up to max_events entries are written in
+ * the order they happen (START / PROMOTE / RELEASE carry one block each; DIT_DONE carries the
+ * request's lowest GPU and its parallel size); *n_events_out is the number that occurred, which
+ * may exceed max_events.  totals: sum over GPUs of occupied time, and the time of the last event. */
+int ddit_sched_simulate(const ddit_sched_config *config, const ddit_sched_request *requests_host, int32_t n_requests,
+                        ddit_sched_record *records_out, ddit_sched_event *events_out_or_null, int64_t max_events,
+                        int64_t *n_events_out, ddit_sched_totals *totals_out);
 
 #ifdef __cplusplus
 }

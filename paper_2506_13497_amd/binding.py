@@ -28,7 +28,9 @@ EXPORTS = ["ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_wo
            "ddit_linear_fwd", "ddit_timestep_conditioning", "ddit_io_workspace_bytes", "ddit_embed_latent",
            "ddit_embed_caption", "ddit_output_head", "ddit_eps_theta", "ddit_solver_step", "ddit_sample",
            "ddit_cross_kv_bytes", "ddit_cross_kv_precompute", "ddit_denoise_step_cached", "ddit_linear_tile_count",
-           "ddit_linear_tile_info", "ddit_linear_tile_choice", "ddit_linear_fwd_tile", "ddit_qk_norm_rope_fwd"]
+           "ddit_linear_tile_info", "ddit_linear_tile_choice", "ddit_linear_fwd_tile", "ddit_qk_norm_rope_fwd", "ddit_optimal_dop",
+           "ddit_buddy_create", "ddit_buddy_alloc", "ddit_buddy_release", "ddit_buddy_free_gpus", "ddit_buddy_destroy",
+           "ddit_sched_simulate"]
 
 
 class ddit_shape(C.Structure):
@@ -61,6 +63,33 @@ _IO_FIELDS = ["w_patch", "b_patch", "w_y1", "b_y1", "w_y2", "b_y2", "final_table
 class ddit_io_weights(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("C_in", C.c_int32), ("C_out", C.c_int32), ("C_text", C.c_int32)] + \
                [(n, C.c_void_p) for n in _IO_FIELDS]
+
+
+class ddit_sched_config(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("n_gpus", C.c_int32), ("n_steps", C.c_int32), ("n_resolutions", C.c_int32),
+                ("n_dop", C.c_int32), ("vae_gpus", C.c_int32), ("step_us", C.POINTER(C.c_int64)),
+                ("opt_dop", C.POINTER(C.c_int32)), ("vae_us", C.POINTER(C.c_int64))]
+
+
+class ddit_sched_request(C.Structure):
+    _fields_ = [("arrival_us", C.c_int64), ("resolution", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ddit_sched_record(C.Structure):
+    _fields_ = [("start_us", C.c_int64), ("dit_end_us", C.c_int64), ("end_us", C.c_int64), ("starvation", C.c_int64),
+                ("first_dop", C.c_int32), ("final_dop", C.c_int32), ("promotions", C.c_int32), ("reserved", C.c_int32)]
+
+
+class ddit_sched_event(C.Structure):
+    _fields_ = [("time_us", C.c_int64), ("kind", C.c_int32), ("request", C.c_int32), ("gpu_start", C.c_int32),
+                ("gpu_count", C.c_int32)]
+
+
+class ddit_sched_totals(C.Structure):
+    _fields_ = [("occupancy_gpu_us", C.c_int64), ("makespan_us", C.c_int64)]
+
+
+SCHED_EVENT_NAMES = ["start", "promote", "dit_done", "release"]
 
 
 class DditError(RuntimeError):
@@ -96,6 +125,15 @@ def _load() -> C.CDLL:
                                     C.c_int64, C.c_void_p]
     lib.ddit_qk_norm_rope_fwd.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                           C.c_float, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.ddit_optimal_dop.argtypes = [C.POINTER(C.c_int64), C.c_int32, C.c_int64, C.c_int64, C.POINTER(C.c_int32)]
+    lib.ddit_buddy_create.argtypes = [C.c_int32, C.POINTER(C.c_void_p)]
+    lib.ddit_buddy_alloc.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+    lib.ddit_buddy_release.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+    lib.ddit_buddy_free_gpus.argtypes = [C.c_void_p, C.POINTER(C.c_int32)]
+    lib.ddit_buddy_destroy.argtypes = [C.c_void_p]
+    lib.ddit_sched_simulate.argtypes = [C.POINTER(ddit_sched_config), C.POINTER(ddit_sched_request), C.c_int32,
+                                        C.POINTER(ddit_sched_record), C.POINTER(ddit_sched_event), C.c_int64,
+                                        C.POINTER(C.c_int64), C.POINTER(ddit_sched_totals)]
     lib.ddit_linear_fwd_tile.argtypes = [C.c_int] + list(lib.ddit_linear_fwd.argtypes)
     lib.ddit_linear_tile_count.argtypes = []
     lib.ddit_linear_tile_info.argtypes = [C.c_int] + [C.POINTER(C.c_int32)] * 4
@@ -235,6 +273,67 @@ def ddit_linear_fwd(epilogue: int, u, ld_u: int, W, bias, N: int, n: int, k: int
 def ddit_qk_norm_rope_fwd(qk, ld: int, N: int, H: int, dh: int, g_q, g_k, eps: float, S: int, T: int,
                           rope_table=None) -> None:
     _check(_lib.ddit_qk_norm_rope_fwd(_ptr(qk), ld, N, H, dh, _ptr(g_q), _ptr(g_k), eps, S, T, _ptr(rope_table), _stream()))
+
+
+def ddit_optimal_dop(step_us_row: Sequence[int], z_min_num: int = 0, z_min_den: int = 1) -> int:
+    row = (C.c_int64 * len(step_us_row))(*[int(v) for v in step_us_row])
+    out = C.c_int32()
+    _check(_lib.ddit_optimal_dop(row, len(step_us_row), z_min_num, z_min_den, C.byref(out)))
+    return out.value
+
+
+def ddit_buddy_create(n_gpus: int):
+    h = C.c_void_p()
+    _check(_lib.ddit_buddy_create(n_gpus, C.byref(h)))
+    return h
+
+
+def ddit_buddy_alloc(pool, size: int) -> int:
+    """-> start of the block, or -1 when nothing fits."""
+    out = C.c_int32()
+    _check(_lib.ddit_buddy_alloc(pool, size, C.byref(out)))
+    return out.value
+
+
+def ddit_buddy_release(pool, start: int, size: int) -> None:
+    _check(_lib.ddit_buddy_release(pool, start, size))
+
+
+def ddit_buddy_free_gpus(pool) -> int:
+    out = C.c_int32()
+    _check(_lib.ddit_buddy_free_gpus(pool, C.byref(out)))
+    return out.value
+
+
+def ddit_buddy_destroy(pool) -> None:
+    _check(_lib.ddit_buddy_destroy(pool))
+
+
+def ddit_sched_simulate(n_gpus: int, n_steps: int, step_us: Sequence[Sequence[int]], opt_dop: Sequence[int],
+                        requests: Sequence[Sequence[int]], vae_us: Optional[Sequence[int]] = None, vae_gpus: int = 1,
+                        max_events: Optional[int] = None):
+    """requests: (arrival_us, resolution) pairs -> (records, events, totals) as plain dicts / tuples."""
+    R, K = len(step_us), len(step_us[0])
+    flat = (C.c_int64 * (R * K))(*[int(v) for row in step_us for v in row])
+    bb = (C.c_int32 * R)(*[int(v) for v in opt_dop])
+    vv = None if vae_us is None else (C.c_int64 * R)(*[int(v) for v in vae_us])
+    cfg = ddit_sched_config(C.sizeof(ddit_sched_config), n_gpus, n_steps, R, K, vae_gpus, flat, bb, vv)
+    n = len(requests)
+    rq = (ddit_sched_request * max(n, 1))()
+    for i, (a, r) in enumerate(requests):
+        rq[i].arrival_us, rq[i].resolution = int(a), int(r)
+    recs = (ddit_sched_record * max(n, 1))()
+    cap = max_events if max_events is not None else n * (4 + 3 * max(K, 1) + 2 * n_gpus.bit_length()) + 8
+    ev = (ddit_sched_event * max(cap, 1))()
+    n_ev = C.c_int64()
+    tot = ddit_sched_totals()
+    _check(_lib.ddit_sched_simulate(C.byref(cfg), rq, n, recs, ev if cap > 0 else None, cap, C.byref(n_ev), C.byref(tot)))
+    names = ("start_us", "dit_end_us", "end_us", "first_dop", "final_dop", "promotions", "starvation")
+    records = [{k: getattr(recs[i], k) for k in names} for i in range(n)]
+    events = [(ev[i].time_us, SCHED_EVENT_NAMES[ev[i].kind], ev[i].request, ev[i].gpu_start, ev[i].gpu_count)
+              for i in range(min(n_ev.value, cap))]
+    return records, events, {"occupancy_gpu_us": tot.occupancy_gpu_us, "makespan_us": tot.makespan_us,
+                             "n_events": n_ev.value}
 
 
 def ddit_linear_tile_count() -> int:
