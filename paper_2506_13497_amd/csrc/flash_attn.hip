@@ -9,8 +9,13 @@
 //   temporal - group = (b,s): T rows a frame apart (generic fallback; the dedicated
 //              kernel in temporal_attn.hip is the fast path for short T)
 //
-// Work split.  grid = (query tiles of 128, heads, groups); 4 wavefronts per workgroup,
-// each owning 32 queries against all keys of the group.
+// Work split.  Streaming form: grid = (query tiles of 128, heads, groups); 4 wavefronts per
+// workgroup, each owning 32 queries against all keys of the group, K/V tiles through a two-stage
+// LDS ring.  Resident form (key sequences of at most 320 shared by thousands of queries: the text
+// tokens of cross-attention): 8 wavefronts, one workgroup per CU; the unit's whole K and V are
+// fetched into LDS once and the workgroup walks over a run of 256-query tiles with no further tile
+// load and no barrier (480p cross-attention: 0.149 -> 0.109 ms; each further key tile then costs
+// what its MFMAs cost).
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_bf16, 64-wide wavefronts).  Scores are
 // computed transposed, S^T = K Q^T: the K tile is the first operand (read from LDS, 16
@@ -49,12 +54,10 @@
 
 namespace {
 
-#ifndef FA_NW
-#define FA_NW 4
-#endif
-constexpr int NW = FA_NW;      // wavefronts per workgroup
-constexpr int QT = 32 * NW;    // queries per workgroup
-constexpr int KT = 64;    // keys per LDS tile
+constexpr int STREAM_NW = 4;   // wavefronts per workgroup of the streaming form (two workgroups per CU)
+constexpr int RES_NW = 8;      // ... of the resident form (one workgroup per CU)
+constexpr int RES_TILES = 5;   // key tiles the resident form keeps in LDS: sequences of up to 320 keys
+constexpr int KT = 64;         // keys per LDS tile
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 typedef __attribute__((address_space(1))) const void *gbl_ptr_t;
@@ -71,6 +74,7 @@ struct FlashParams {
   int64_t q_tok_step, kv_tok_step;
   int Lq, Lk_max, H;
   int n_qtiles, n_units;   // query tiles per (group, head) unit; units = groups * heads
+  int n_chunks, qtiles_per_chunk;   // resident form: workgroups per unit, consecutive query tiles per workgroup
   int spread;              // few units: spread a unit's query tiles over the XCDs
   int use_kv_len;
   int kv_len[64];
@@ -121,9 +125,17 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 template <bool V>
 struct BoolTag { static constexpr bool value = V; };
 
-template <int DH>
+// RES = false, the streaming form: one query tile per workgroup, K/V tiles through a two-stage ring.
+// RES = true, the resident form, for short key sequences shared by many queries (the text tokens of
+// cross-attention): the whole K and V of the unit are fetched into LDS once (stage t = key tile t),
+// then the workgroup walks over its run of query tiles with no further tile load and no barrier;
+// what it saves is the per-query-tile prologue (with five key tiles that is a third of the time)
+// and four fifths of the K/V traffic.
+template <int DH, int NW, bool RES>
 __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
   using C = Cfg<DH>;
+  constexpr int QT = 32 * NW;              // queries per workgroup and query tile
+  constexpr int NST = RES ? RES_TILES : 2; // LDS stages
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lh = lane >> 5;
@@ -143,8 +155,12 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
   // query tiles consecutive there.
   // (With only a few units that would leave XCDs idle; their K/V are then small enough for every
   // L2, and consecutive workgroups simply take consecutive query tiles.)
-  int unit, qtile;
-  if (p.spread) {
+  int unit, qtile, qt_end;
+  if constexpr (RES) {
+    unit = blockIdx.x / p.n_chunks;
+    qtile = (blockIdx.x - unit * p.n_chunks) * p.qtiles_per_chunk;
+    qt_end = qtile + p.qtiles_per_chunk < p.n_qtiles ? qtile + p.qtiles_per_chunk : p.n_qtiles;
+  } else if (p.spread) {
     unit = blockIdx.x / p.n_qtiles;
     qtile = blockIdx.x - unit * p.n_qtiles;
   } else {
@@ -152,13 +168,13 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
     unit = (idx / p.n_qtiles) * 8 + xcd;
     qtile = idx % p.n_qtiles;
   }
-  if (unit >= p.n_units) return;
+  if constexpr (!RES) qt_end = qtile + 1;
+  if (unit >= p.n_units || qtile >= qt_end) return;
   const int h = unit % p.H, g = unit / p.H;
   const int g_out = g / p.g_inner, g_in = g - g_out * p.g_inner;
   const int Lk = p.use_kv_len ? p.kv_len[g_out] : p.Lk_max;
   const int64_t q_tok0 = p.q_outer * g_out + p.q_inner * g_in;
   const int64_t kv_tok0 = p.kv_outer * g_out + p.kv_inner * g_in;
-  const int q0 = qtile * QT + wave * 32;
   const bf16_t *kbase = p.k + kv_tok0 * p.ld_kv + h * DH;
   const bf16_t *vbase = p.v + kv_tok0 * p.ld_kv + h * DH;
   const int64_t kv_row = p.kv_tok_step * p.ld_kv;   // elements between consecutive keys
@@ -167,8 +183,8 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
   // carry minus the query's reference score, against a K column of ones; the columns past it stay
   // zero.
   bf16x8 qf[C::KS];
-  {
-    int qi = q0 + l32;
+  auto load_q = [&](int q0_) {
+    int qi = q0_ + l32;
     if (qi > p.Lq - 1) qi = p.Lq - 1;
     const bf16_t *qrow = p.q + (q_tok0 + (int64_t)qi * p.q_tok_step) * p.ld_q + h * DH;
 #pragma unroll
@@ -178,7 +194,8 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
       for (int e = 0; e < 8; ++e) qf[ks][e] = (bf16_t)0.f;
       if (d0 < DH) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + d0);
     }
-  }
+  };
+  load_q(qtile * QT + wave * 32);
   constexpr int KS_REF = DH / 16;                       // k-step of the reference column
   const bool ref_lane = (8 * lh == DH - 16 * KS_REF);   // lanes whose fragment of that k-step starts at column DH
 
@@ -193,15 +210,17 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
       k_off[ks][hf] = c < C::DCH ? row * C::KROW + (C::SWZ ? (c ^ (row & 7)) : c) * 16 : C::KCONST;
     }
   static_assert(C::VONE == C::KCONST + 16 && C::OVERRUN >= 24, "the first piece of ones lies in the slack after the K piece");
-  if (tid < 2 * (C::OVERRUN / 4)) {
+  static_assert(NST * (C::OVERRUN / 4) + NST * 6 <= 64 * NW, "one thread per constant word");
+  if (tid < NST * (C::OVERRUN / 4)) {
     // per stage, the 64 bytes after the V tile: the constant K piece (1, 0, ..., 0), the first
     // (1, 0, 0, 0) piece of V^T's row of ones, zeros in the rest (padded V^T rows read it); every
     // word has exactly one writer
     const int st = tid / (C::OVERRUN / 4), w = tid - st * (C::OVERRUN / 4);
     *reinterpret_cast<unsigned *>(smem + st * C::STAGE + C::KCONST + 4 * w) =
         (w == 0 || (C::ONES && w == 4)) ? 0x00003F80u : 0u;
-  } else if (C::ONES && tid >= 32 && tid < 32 + 2 * 3 * 2) {   // the other three pieces of ones, 16 keys apart
-    const int e = tid - 32, st = e / 6, kc = 1 + (e % 6) / 2, w = e & 1;
+  } else if (C::ONES && tid >= NST * (C::OVERRUN / 4) && tid < NST * (C::OVERRUN / 4) + NST * 6) {
+    // the other three pieces of ones, 16 keys apart
+    const int e = tid - NST * (C::OVERRUN / 4), st = e / 6, kc = 1 + (e % 6) / 2, w = e & 1;
     *reinterpret_cast<unsigned *>(smem + st * C::STAGE + C::VONE + kc * 16 * C::KROW + 4 * w) = w == 0 ? 0x00003F80u : 0u;
   }
 
@@ -301,13 +320,13 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
   // (32 clocks in the matrix core, dependent on the one two slots earlier) is followed by a slice
   // of VALU work that does not depend on it; the exponentials of tile it and the MFMAs of both
   // products then run side by side instead of one after the other.
-  auto tile_step = [&](auto next_tag, bool first, int cur, floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2]) {
+  auto tile_step = [&](auto next_tag, bool first, int k_stage, int v_stage, floatx16 (&s_cur)[2], floatx16 (&s_nxt)[2]) {
     constexpr bool NEXT = decltype(next_tag)::value;
     constexpr int NQ = NEXT ? 2 * C::KS : 0;      // MFMAs of the next tile's scores
     constexpr int NPV = 4 * C::DT;                // MFMAs of this tile's O update
     constexpr int M = NQ + NPV;
-    const unsigned char *sk = smem + (cur ^ 1) * C::STAGE;            // K of tile it+1
-    const unsigned char *sv = smem + cur * C::STAGE + C::T_BYTES;     // V of tile it
+    const unsigned char *sk = smem + k_stage * C::STAGE;              // K of tile it+1
+    const unsigned char *sv = smem + v_stage * C::STAGE + C::T_BYTES; // V of tile it
     bf16x8 kf[NEXT ? NQ : 1];
     if constexpr (NEXT) {
 #pragma unroll
@@ -452,115 +471,162 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
 #undef FA_SLOT_QK
   };
 
-  // Software pipeline over the key tiles.  Stage it & 1 holds K and V of tile it.  K of tile it is
-  // dead once its scores exist (formed during tile it-1), so K of tile it+2 is fetched at the start
-  // of tile it; V of tile it is used until the end of tile it, so V of tile it+2 follows after the
-  // barrier that ends tile it.  Both have a whole tile's time to land.
+  // Software pipeline over the key tiles (streaming form).  Stage it & 1 holds K and V of tile it.  K
+  // of tile it is dead once its scores exist (formed during tile it-1), so K of tile it+2 is fetched at
+  // the start of tile it; V of tile it is used until the end of tile it, so V of tile it+2 follows
+  // after the barrier that ends tile it.  Both have a whole tile's time to land.
+  // Resident form: every tile is fetched here, once, and stays.
   const int n_tiles = (Lk + KT - 1) / KT;
-  FA_LOAD(0, 0, 0, 0);
-  FA_LOAD(1, 0, 0, 0);
-  if (n_tiles > 1) {
-    FA_LOAD(0, KT, 1, 1);
-    FA_LOAD(1, KT, 1, 1);
+  if constexpr (RES) {
+    for (int t = 0; t < n_tiles; ++t) {
+      FA_LOAD(0, t * KT, t, t);
+      FA_LOAD(1, t * KT, t, t);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // tile 0 has landed (once per kernel: also waits tile 1)
-  lds_barrier();
-  FA_QK(s_a, 0);
-  lds_barrier();                                      // K of tile 0 may now be overwritten (by tile 2)
 
 #define FA_ITER(HAS_NEXT, S_CUR, S_NXT)                                                                 \
   do {                                                                                                  \
-    const int cur_ = it & 1;                                                                            \
-    if (it + 2 < n_tiles) FA_LOAD(0, (it + 2) * KT, cur_, it + 2);                                      \
+    const int cur_ = RES ? it : (it & 1);                                                               \
+    if constexpr (!RES) {                                                                               \
+      if (it + 2 < n_tiles) FA_LOAD(0, (it + 2) * KT, cur_, it + 2);                                    \
+    }                                                                                                   \
     FENCE();                                                                                            \
-    tile_step(BoolTag<HAS_NEXT>{}, it == 0, cur_, S_CUR, S_NXT);                                                 \
+    tile_step(BoolTag<HAS_NEXT>{}, it == 0, RES ? it + 1 : (cur_ ^ 1), cur_, S_CUR, S_NXT);             \
     FENCE();                                                                                            \
-    if (HAS_NEXT) {                                                                                     \
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K of tile it+2 (and V of tile it+1) has landed */ \
-      lds_barrier(); /* V of tile it, K of tile it+1 are free; tile it+1's V and tile it+2's K complete */ \
-      if (it + 2 < n_tiles) FA_LOAD(1, (it + 2) * KT, cur_, it + 2);                                    \
+    if constexpr (!RES) {                                                                               \
+      if (HAS_NEXT) {                                                                                   \
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); /* K of tile it+2 (and V of tile it+1) has landed */ \
+        lds_barrier(); /* V of tile it, K of tile it+1 are free; tile it+1's V and tile it+2's K complete */ \
+        if (it + 2 < n_tiles) FA_LOAD(1, (it + 2) * KT, cur_, it + 2);                                  \
+      }                                                                                                 \
     }                                                                                                   \
   } while (0)
 
-  int it = 0;
-  for (; it + 2 < n_tiles; it += 2) {
-    FA_ITER(true, s_a, s_b);
-    ++it;
-    FA_ITER(true, s_b, s_a);
-    --it;
-  }
-  // ---- one or two tiles left; the last one masks the keys past the end
-  auto mask_tail = [&](floatx16 (&sc)[2]) {
-    const int key0 = it * KT;
-    if (key0 + KT > Lk) {
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-          if (key >= Lk) sc[kt][r] = -INFINITY;
-        }
+  for (;;) {   // over this workgroup's query tiles (the streaming form has one)
+    const int q0 = qtile * QT + wave * 32;
+    if constexpr (!RES) {
+      FA_LOAD(0, 0, 0, 0);
+      FA_LOAD(1, 0, 0, 0);
+      if (n_tiles > 1) {
+        FA_LOAD(0, KT, 1, 1);
+        FA_LOAD(1, KT, 1, 1);
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // tile 0 has landed (once per kernel: also waits tile 1)
+      lds_barrier();
     }
-  };
-  if (it + 1 < n_tiles) {
-    FA_ITER(true, s_a, s_b);
-    ++it;
-    mask_tail(s_b);
-    FA_ITER(false, s_b, s_a);
-  } else {
-    mask_tail(s_a);
-    FA_ITER(false, s_a, s_b);
+    FA_QK(s_a, 0);
+    if constexpr (!RES) lds_barrier();                    // K of tile 0 may now be overwritten (by tile 2)
+
+    int it = 0;
+    for (; it + 2 < n_tiles; it += 2) {
+      FA_ITER(true, s_a, s_b);
+      ++it;
+      FA_ITER(true, s_b, s_a);
+      --it;
+    }
+    // ---- one or two tiles left; the last one masks the keys past the end
+    auto mask_tail = [&](floatx16 (&sc)[2]) {
+      const int key0 = it * KT;
+      if (key0 + KT > Lk) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+            if (key >= Lk) sc[kt][r] = -INFINITY;
+          }
+      }
+    };
+    if (it + 1 < n_tiles) {
+      FA_ITER(true, s_a, s_b);
+      ++it;
+      mask_tail(s_b);
+      FA_ITER(false, s_b, s_a);
+    } else {
+      mask_tail(s_a);
+      FA_ITER(false, s_a, s_b);
+    }
+
+    // ---- row sum
+    float l_tot;
+    if (C::ONES) {
+      // V^T row DH lives in tile DH/32, accumulator register 4*((DH%32)/8) of the lanes with lh == 0
+      constexpr int dt = DH / 32, reg = 4 * ((DH % 32) / 8);
+      l_tot = __shfl(oacc[dt][reg], l32, 64);
+    } else {
+      l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    }
+    const float inv = 1.0f / l_tot;
+    const int qi = q0 + l32;
+    if (qi < p.Lq) {
+      const int64_t tok = q_tok0 + (int64_t)qi * p.q_tok_step;
+      bf16_t *orow = p.o + tok * p.ld_o + h * DH;
+#pragma unroll
+      for (int d = 0; d < C::DT; ++d)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const int d0 = 32 * d + 8 * gq + 4 * lh;
+          if (d0 < DH) {
+            bf16x4 ov;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(oacc[d][4 * gq + e] * inv);
+            *reinterpret_cast<bf16x4 *>(orow + d0) = ov;
+          }
+        }
+      if (p.lse && lh == 0) p.lse[tok * p.H + h] = m_ref * p.scale + __logf(l_tot);
+    }
+    if constexpr (!RES) {
+      break;
+    } else {
+      if (++qtile >= qt_end) break;
+      // next query tile of the run: fresh queries (their reference column is zero again), empty sums
+      // (fetching them earlier, under the last key tile, costs 20 registers the kernel does not have:
+      // measured with the spills it causes, 0.131 ms against 0.109 ms; the second wavefront of the
+      // SIMD covers the wait instead)
+      load_q(qtile * QT + wave * 32);
+#pragma unroll
+      for (int d = 0; d < C::DT; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[d][e] = 0.f;
+      m_ref = 0.f;
+      l_run = 0.f;
+    }
   }
 #undef FA_ITER
 #undef FENCE
 #undef FA_QK
 #undef FA_LOAD
-
-  // ---- row sum
-  float l_tot;
-  if (C::ONES) {
-    // V^T row DH lives in tile DH/32, accumulator register 4*((DH%32)/8) of the lanes with lh == 0
-    constexpr int dt = DH / 32, reg = 4 * ((DH % 32) / 8);
-    l_tot = __shfl(oacc[dt][reg], l32, 64);
-  } else {
-    l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  }
-  const float inv = 1.0f / l_tot;
-  const int qi = q0 + l32;
-  if (qi < p.Lq) {
-    const int64_t tok = q_tok0 + (int64_t)qi * p.q_tok_step;
-    bf16_t *orow = p.o + tok * p.ld_o + h * DH;
-#pragma unroll
-    for (int d = 0; d < C::DT; ++d)
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        const int d0 = 32 * d + 8 * gq + 4 * lh;
-        if (d0 < DH) {
-          bf16x4 ov;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(oacc[d][4 * gq + e] * inv);
-          *reinterpret_cast<bf16x4 *>(orow + d0) = ov;
-        }
-      }
-    if (p.lse && lh == 0) p.lse[tok * p.H + h] = m_ref * p.scale + __logf(l_tot);
-  }
 }
 
-template <int DH>
-int launch_dh(const FlashParams &p, int n_groups, hipStream_t s) {
+template <int DH, int NW, bool RES>
+int launch_dh(const FlashParams &p, int64_t blocks, hipStream_t s) {
   using C = Cfg<DH>;
-  constexpr int smem = 2 * C::STAGE;
+  constexpr int smem = (RES ? RES_TILES : 2) * C::STAGE;
+  static_assert(smem <= 160 * 1024, "the stages must fit the LDS");
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_flash_attn<DH>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_flash_attn<DH, NW, RES>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return ddit::hip_fail(e, "flash hipFuncSetAttribute");
     attr_set = true;
   }
-  const int64_t blocks = (p.spread ? (int64_t)p.n_units : (int64_t)((p.n_units + 7) / 8) * 8) * p.n_qtiles;
   if (blocks > 0x7fffffff) { ddit::set_error("attention: too many workgroups"); return -2; }
-  hipLaunchKernelGGL(k_flash_attn<DH>, dim3((unsigned)blocks), dim3(64 * NW), smem, s, p);
+  hipLaunchKernelGGL((k_flash_attn<DH, NW, RES>), dim3((unsigned)blocks), dim3(64 * NW), smem, s, p);
   return ddit::hip_fail(hipGetLastError(), "flash attention launch");
+}
+
+int num_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cus = prop.multiProcessorCount;
+    if (cus <= 0) cus = 256;
+  }
+  return cus;
 }
 
 }  // namespace
@@ -589,11 +655,28 @@ int launch_flash_attn(const AttnArgs &a, hipStream_t s) {
     set_error("attention grid too large (groups=%d heads=%d)", a.n_groups, a.H);
     return -2;
   }
-  p.n_qtiles = (a.Lq + QT - 1) / QT;
   p.n_units = a.n_groups * a.H;
+  p.n_chunks = 1; p.qtiles_per_chunk = 1;
+  // Short key sequences shared by long query sequences (cross-attention to the text): the resident
+  // form, when every workgroup gets a run of at least four query tiles to spread the one-off K/V
+  // fetch over.  One workgroup per CU: as many chunks per unit as that allows.
+  const int res_qtiles = (a.Lq + 32 * RES_NW - 1) / (32 * RES_NW);
+  int chunks = num_cus() / (p.n_units > 0 ? p.n_units : 1);
+  if (chunks < 1) chunks = 1;
+  if (a.Lk_max <= RES_TILES * KT && res_qtiles >= 4 * chunks) {
+    p.n_qtiles = res_qtiles;
+    p.qtiles_per_chunk = (res_qtiles + chunks - 1) / chunks;
+    p.n_chunks = (res_qtiles + p.qtiles_per_chunk - 1) / p.qtiles_per_chunk;
+    p.spread = 0;
+    const int64_t blocks = (int64_t)p.n_units * p.n_chunks;
+    if (a.dh == 72) return launch_dh<72, RES_NW, true>(p, blocks, s);
+    if (a.dh == 64) return launch_dh<64, RES_NW, true>(p, blocks, s);
+  }
+  p.n_qtiles = (a.Lq + 32 * STREAM_NW - 1) / (32 * STREAM_NW);
   p.spread = p.n_units < 64;
-  if (a.dh == 72) return launch_dh<72>(p, a.n_groups, s);
-  if (a.dh == 64) return launch_dh<64>(p, a.n_groups, s);
+  const int64_t blocks = (p.spread ? (int64_t)p.n_units : (int64_t)((p.n_units + 7) / 8) * 8) * p.n_qtiles;
+  if (a.dh == 72) return launch_dh<72, STREAM_NW, false>(p, blocks, s);
+  if (a.dh == 64) return launch_dh<64, STREAM_NW, false>(p, blocks, s);
   set_error("dh=%d: supported head dims are 64 and 72", a.dh);
   return -2;
 }

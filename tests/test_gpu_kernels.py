@@ -298,6 +298,24 @@ def test_cross_attention_batch2_masks(lib):
     _attn_case(lib, "cross", sh, valid=[45, 290], Lq=200)
 
 
+# Short text sequences shared by many queries take the resident form of the kernel (all K/V tiles of a
+# (sample, head) unit fetched once, the workgroup walking over a run of query tiles): it is chosen when a
+# unit has at least four 256-query tiles per workgroup, at one workgroup per CU.  These shapes reach it on
+# a 256-CU device (and are valid cases for the streaming form on any other).
+@pytest.mark.parametrize("B,Lq,Ly,H,dh,valid,q_scale", [
+    (64, 1000, 100, 4, 64, "mixed", 1.0),       # 256 units, one workgroup each, four query tiles, ragged last one
+    (2, 8200, 300, 16, 72, [287, 33], 1.0),     # 32 units x 7 workgroups with runs of 5 (last: 3) query tiles
+    (2, 8200, 300, 16, 72, [300, 1], 4.0),      # peaked scores; a single valid key
+    (64, 1024, 320, 4, 72, None, 1.0),          # five full key tiles: the longest resident sequence
+    (64, 1024, 321, 4, 72, None, 1.0),          # one key more: streaming form
+], ids=["b64-dh64", "b2-h16", "b2-h16-peaked", "ly320", "ly321"])
+def test_cross_attention_many_queries(lib, B, Lq, Ly, H, dh, valid, q_scale):
+    sh = syn.Shape(B, 1, 1, Lq, H * dh, H, dh, 64, Ly, 1)
+    if valid == "mixed":
+        valid = [1 + (37 * b) % Ly for b in range(B)]
+    _attn_case(lib, "cross", sh, valid=valid, Lq=Lq, q_scale=q_scale, seed=3)
+
+
 # ---- closed forms and invariances, on the GPU
 def test_values_of_ones_give_ones(lib):
     sh = SELF_SHAPES[2]
