@@ -328,6 +328,10 @@ def ddit_sched_simulate(n_gpus: int, n_steps: int, step_us: Sequence[Sequence[in
     n_ev = C.c_int64()
     tot = ddit_sched_totals()
     _check(_lib.ddit_sched_simulate(C.byref(cfg), rq, n, recs, ev if cap > 0 else None, cap, C.byref(n_ev), C.byref(tot)))
+    if max_events is None and n_ev.value > cap:          # the estimate was short: run again with the exact size
+        cap = n_ev.value
+        ev = (ddit_sched_event * cap)()
+        _check(_lib.ddit_sched_simulate(C.byref(cfg), rq, n, recs, ev, cap, C.byref(n_ev), C.byref(tot)))
     names = ("start_us", "dit_end_us", "end_us", "first_dop", "final_dop", "promotions", "starvation")
     records = [{k: getattr(recs[i], k) for k in names} for i in range(n)]
     events = [(ev[i].time_us, SCHED_EVENT_NAMES[ev[i].kind], ev[i].request, ev[i].gpu_start, ev[i].gpu_count)

@@ -32,6 +32,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 namespace ddit {
 void set_error(const char *fmt, ...);
 int hip_fail(hipError_t e, const char *what);
+int device_cus();   // compute units of the current device (cached per process; 256 if there is no device)
 
 // kernel launchers (each validates nothing: callers have validated shapes)
 int launch_modulated_layernorm(const float *x, const float *ada_table, const float *c6, int which, int64_t N,

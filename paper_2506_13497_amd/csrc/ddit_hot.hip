@@ -26,6 +26,17 @@ int hip_fail(hipError_t e, const char *what) {
   return DDIT_ERR_HIP;
 }
 
+int device_cus() {
+  static int cus = 0;   // benign race: every thread computes the same value
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
+    cus = n > 0 ? n : 256;
+  }
+  return cus;
+}
+
 namespace {
 
 inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }

@@ -617,18 +617,6 @@ int launch_dh(const FlashParams &p, int64_t blocks, hipStream_t s) {
   return ddit::hip_fail(hipGetLastError(), "flash attention launch");
 }
 
-int num_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-      cus = prop.multiProcessorCount;
-    if (cus <= 0) cus = 256;
-  }
-  return cus;
-}
-
 }  // namespace
 
 namespace ddit {
@@ -661,7 +649,7 @@ int launch_flash_attn(const AttnArgs &a, hipStream_t s) {
   // form, when every workgroup gets a run of at least four query tiles to spread the one-off K/V
   // fetch over.  One workgroup per CU: as many chunks per unit as that allows.
   const int res_qtiles = (a.Lq + 32 * RES_NW - 1) / (32 * RES_NW);
-  int chunks = num_cus() / (p.n_units > 0 ? p.n_units : 1);
+  int chunks = ddit::device_cus() / (p.n_units > 0 ? p.n_units : 1);
   if (chunks < 1) chunks = 1;
   if (a.Lk_max <= RES_TILES * KT && res_qtiles >= 4 * chunks) {
     p.n_qtiles = res_qtiles;

@@ -620,18 +620,6 @@ __global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
   }
 }
 
-int num_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-      cus = prop.multiProcessorCount;
-    if (cus <= 0) cus = 256;
-  }
-  return cus;
-}
-
 template <int WGM, int WGN, int TM, int TN, int NS, int EPI>
 int launch_one(const GemmParams &p0, hipStream_t s) {
   using C = GemmCfg<WGM, WGN, TM, TN, NS>;
@@ -657,7 +645,7 @@ int launch_one(const GemmParams &p0, hipStream_t s) {
   p.total_tiles = (int)total;
   // as many workgroups as the chip holds at once; a multiple of 8 so that every round gives
   // each XCD a contiguous run of tiles
-  int grid = (num_cus() * WG_PER_CU) & ~7;
+  int grid = (ddit::device_cus() * WG_PER_CU) & ~7;
   if (grid < 8) grid = 8;
   if (total <= grid) grid = (int)((total + 7) & ~(int64_t)7);
   p.rounds = (int)(((total + 7) / 8 + grid / 8 - 1) / (grid / 8));
@@ -739,7 +727,7 @@ int launch_checked(int tile, const GemmParams &p, hipStream_t s) {
 
 template <int EPI>
 int launch_epi(int tile, const GemmParams &p, hipStream_t s) {
-  if (tile < 0) tile = cheapest_tile(EPI, p.N, p.n, p.k, num_cus());
+  if (tile < 0) tile = cheapest_tile(EPI, p.N, p.n, p.k, ddit::device_cus());
   switch (tile) {
     case 0: return launch_checked<2, 4, 3, 3, EPI>(tile, p, s);
     case 1: return launch_checked<2, 3, 3, 3, EPI>(tile, p, s);
@@ -767,7 +755,7 @@ int gemm_tile_info(int tile, int *rows, int *cols, int *wavefronts, int *wg_per_
 }
 
 int gemm_tile_choice(int epilogue, int64_t N, int n, int k, int cus, float *us_per_tile) {
-  if (cus <= 0) cus = num_cus();
+  if (cus <= 0) cus = ddit::device_cus();
   if (us_per_tile)
     for (int t = 0; t < N_TILES; ++t) us_per_tile[t] = predicted_us(t, epilogue, N, n, k, cus);
   return cheapest_tile(epilogue, N, n, k, cus);
