@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-#define DDIT_ABI_VERSION 5u
+#define DDIT_ABI_VERSION 6u
 
 typedef enum {
   DDIT_OK = 0,
@@ -214,6 +214,18 @@ int ddit_linear_fwd(int epilogue, const void *u, int64_t ld_u, const void *W, co
 int ddit_qk_norm_rope_fwd(void *qk, int64_t ld, int64_t N, int32_t H, int32_t dh, const void *g_q,
                           const void *g_k, float eps, int64_t S, int32_t T, float *rope_table_or_null,
                           void *hip_stream);
+
+/* Spatial or temporal self-attention with those two options applied to q and k on the way (what a
+ * layer does between its q|k|v projection and its out-projection): per-head RMS normalisation iff
+ * g_q and g_k (bf16 [dh]) are given, with shape->ln_eps; rotation by the frame index iff kind is
+ * TEMPORAL and rope_table_or_null is given (device scratch of T*dh floats, filled by the call).
+ * fuse != 0 folds the treatment into the attention kernels where that is possible (temporal with
+ * T <= 32: wholly; spatial: the queries, while the keys are treated in place first); fuse == 0 treats
+ * q and k in place first and then runs the plain attention.  Either way q and k may be overwritten
+ * with their treated values; v is only read.  Tensors and strides as in ddit_attn_fwd. */
+int ddit_self_attn_fwd(ddit_attn_kind kind, const ddit_shape *shape, void *q, void *k, const void *v, int64_t ld_q,
+                       int64_t ld_kv, const void *g_q, const void *g_k, float *rope_table_or_null, int fuse, void *o,
+                       int64_t ld_o, float *lse_or_null, void *hip_stream);
 
 /* ---- output tiles of the linear: for tuning and for parity tests of every compiled tile ----
  * The linear is compiled for a short list of output tiles (rows x cols of out per workgroup) and

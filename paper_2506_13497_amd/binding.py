@@ -28,7 +28,7 @@ EXPORTS = ["ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_wo
            "ddit_linear_fwd", "ddit_timestep_conditioning", "ddit_io_workspace_bytes", "ddit_embed_latent",
            "ddit_embed_caption", "ddit_output_head", "ddit_eps_theta", "ddit_solver_step", "ddit_sample",
            "ddit_cross_kv_bytes", "ddit_cross_kv_precompute", "ddit_denoise_step_cached", "ddit_linear_tile_count",
-           "ddit_linear_tile_info", "ddit_linear_tile_choice", "ddit_linear_fwd_tile", "ddit_qk_norm_rope_fwd", "ddit_optimal_dop",
+           "ddit_linear_tile_info", "ddit_linear_tile_choice", "ddit_linear_fwd_tile", "ddit_qk_norm_rope_fwd", "ddit_self_attn_fwd", "ddit_optimal_dop",
            "ddit_buddy_create", "ddit_buddy_alloc", "ddit_buddy_release", "ddit_buddy_free_gpus", "ddit_buddy_destroy",
            "ddit_sched_simulate"]
 
@@ -134,6 +134,9 @@ def _load() -> C.CDLL:
     lib.ddit_sched_simulate.argtypes = [C.POINTER(ddit_sched_config), C.POINTER(ddit_sched_request), C.c_int32,
                                         C.POINTER(ddit_sched_record), C.POINTER(ddit_sched_event), C.c_int64,
                                         C.POINTER(C.c_int64), C.POINTER(ddit_sched_totals)]
+    lib.ddit_self_attn_fwd.argtypes = [C.c_int, C.POINTER(ddit_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                       C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int64,
+                                       C.c_void_p, C.c_void_p]
     lib.ddit_linear_fwd_tile.argtypes = [C.c_int] + list(lib.ddit_linear_fwd.argtypes)
     lib.ddit_linear_tile_count.argtypes = []
     lib.ddit_linear_tile_info.argtypes = [C.c_int] + [C.POINTER(C.c_int32)] * 4
@@ -338,6 +341,12 @@ def ddit_sched_simulate(n_gpus: int, n_steps: int, step_us: Sequence[Sequence[in
               for i in range(min(n_ev.value, cap))]
     return records, events, {"occupancy_gpu_us": tot.occupancy_gpu_us, "makespan_us": tot.makespan_us,
                              "n_events": n_ev.value}
+
+
+def ddit_self_attn_fwd(kind: int, shape: ddit_shape, q, k, v, ld_q: int, ld_kv: int, g_q, g_k, rope_table, fuse: bool, o,
+                       ld_o: int, lse=None) -> None:
+    _check(_lib.ddit_self_attn_fwd(kind, C.byref(shape), _ptr(q), _ptr(k), _ptr(v), ld_q, ld_kv, _ptr(g_q), _ptr(g_k),
+                                   _ptr(rope_table), 1 if fuse else 0, _ptr(o), ld_o, _ptr(lse), _stream()))
 
 
 def ddit_linear_tile_count() -> int:

@@ -71,17 +71,24 @@ struct AttnArgs {
   int kv_len[64];                   // per OUTER index (batch) valid key count, used if use_kv_len
   int use_kv_len;
   int H, dh;
+  const void *q_norm_g;             // bf16 [dh] or null: RMS-normalise every query with these scales as it is loaded
+  float q_norm_eps;
 };
 int launch_flash_attn(const AttnArgs &a, hipStream_t s);
 int temporal_attn_max_T();   // longest sequence the dedicated temporal kernel takes
+// g_q/g_k (per-head RMS-norm scales, both or neither) and rope_table ([T, dh/2] (cos, sin)) may be null:
+// when given, q and k are normalised / rotated inside the kernel on their way in
 int launch_temporal_attn(const void *q, const void *k, const void *v, void *o, float *lse, int64_t ld_q,
-                         int64_t ld_kv, int64_t ld_o, int B, int T, int S, int H, int dh, hipStream_t s);
+                         int64_t ld_kv, int64_t ld_o, int B, int T, int S, int H, int dh, const void *g_q,
+                         const void *g_k, float norm_eps, const float *rope_table, hipStream_t s);
 
-// per-head RMS normalisation and rotary embedding of q | k, in place (qk_norm_rope.hip).
+// per-head RMS normalisation and rotary embedding, in place (qk_norm_rope.hip), of `slots` consecutive heads
+// per token row starting at qk: the first q_slots of them take the scales g_q, the others g_k (q | k of a
+// fused projection: slots = 2H, q_slots = H; one operand alone: slots = H, q_slots = H or 0).
 // g_q/g_k null: no normalisation; rope_table null: no rotation
 int launch_rope_table(float *table, int T, int dh, hipStream_t s);   // [T, dh/2] (cos, sin)
-int launch_qk_norm_rope(void *qk, int64_t ld, int64_t N, int H, int dh, const void *g_q, const void *g_k, float eps,
-                        const float *rope_table, int64_t S, int T, hipStream_t s);
+int launch_qk_norm_rope(void *qk, int64_t ld, int64_t N, int slots, int q_slots, int dh, const void *g_q,
+                        const void *g_k, float eps, const float *rope_table, int64_t S, int T, hipStream_t s);
 
 int launch_cast_bf16_to_f32(const void *in, float *out, int64_t n, hipStream_t s);
 int launch_cast_f32_to_bf16(const float *in, void *out, int64_t n, hipStream_t s);

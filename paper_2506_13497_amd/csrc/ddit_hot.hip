@@ -126,11 +126,15 @@ int check_layer_weights(const ddit_layer_weights &w, const char *which, uint32_t
   return DDIT_OK;
 }
 
+// q_norm_g (bf16 [dh] or null): the streaming kernel RMS-normalises the queries with these scales as it
+// loads them (spatial layers with the q/k normalisation option)
 int run_attention(ddit_attn_kind kind, const Dims &d, const void *q, const void *k, const void *v, int64_t ld_q,
-                  int64_t ld_kv, const int32_t *valid_len, void *o, int64_t ld_o, float *lse, hipStream_t s) {
+                  int64_t ld_kv, const int32_t *valid_len, void *o, int64_t ld_o, float *lse, hipStream_t s,
+                  const void *q_norm_g = nullptr, float q_norm_eps = 0.f) {
   AttnArgs a;
   memset(&a, 0, sizeof(a));
   a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+  a.q_norm_g = q_norm_g; a.q_norm_eps = q_norm_eps;
   a.ld_q = ld_q; a.ld_kv = ld_kv; a.ld_o = ld_o;
   a.H = (int)d.H; a.dh = (int)d.dh;
   switch (kind) {
@@ -145,7 +149,7 @@ int run_attention(ddit_attn_kind kind, const Dims &d, const void *q, const void 
       // the generic streaming kernel with strided groups
       if (d.T <= temporal_attn_max_T())
         return launch_temporal_attn(q, k, v, o, lse, ld_q, ld_kv, ld_o, (int)d.B, (int)d.T, (int)d.S, (int)d.H,
-                                    (int)d.dh, s);
+                                    (int)d.dh, nullptr, nullptr, 0.f, nullptr, s);
       a.n_groups = (int)(d.B * d.S); a.g_inner = (int)d.S;
       a.q_outer = a.kv_outer = d.T * d.S; a.q_inner = a.kv_inner = 1;
       a.q_tok_step = a.kv_tok_step = d.S;
@@ -166,6 +170,38 @@ int run_attention(ddit_attn_kind kind, const Dims &d, const void *q, const void 
       return DDIT_ERR_INVALID_ARG;
   }
   return launch_flash_attn(a, s);
+}
+
+// Self-attention with the two optional treatments of q and k (per-head RMS normalisation with scales g_q,
+// g_k, both or neither; rotation by rope_table, temporal only), done where it costs least:
+//   temporal, T within the dedicated kernel: inside that kernel, after the operands have landed in LDS;
+//   spatial: the queries inside the attention kernel as they are loaded, the keys (which every query tile
+//            re-reads) once, in place, by the streaming kernel;
+//   otherwise, or with fuse == false: q and k in place by the streaming kernel, then the plain attention.
+// q and k may therefore be overwritten with their treated values.
+int run_self_attention(ddit_attn_kind kind, const Dims &d, void *q, void *k, const void *v, int64_t ld_q, int64_t ld_kv,
+                       const void *g_q, const void *g_k, float eps, const float *rope_table, bool fuse, void *o,
+                       int64_t ld_o, float *lse, hipStream_t s) {
+  const float *rope = kind == DDIT_ATTN_TEMPORAL ? rope_table : nullptr;
+  if (!g_q && !rope) return run_attention(kind, d, q, k, v, ld_q, ld_kv, nullptr, o, ld_o, lse, s);
+  const int H = (int)d.H, dh = (int)d.dh;
+  if (fuse && kind == DDIT_ATTN_TEMPORAL && d.T <= temporal_attn_max_T())
+    return launch_temporal_attn(q, k, v, o, lse, ld_q, ld_kv, ld_o, (int)d.B, (int)d.T, (int)d.S, H, dh, g_q, g_k, eps,
+                                rope, s);
+  if (fuse && kind == DDIT_ATTN_SPATIAL) {
+    int rc = launch_qk_norm_rope(k, ld_kv, d.N, H, 0, dh, g_q, g_k, eps, nullptr, d.S, (int)d.T, s);
+    if (rc != DDIT_OK) return rc;
+    return run_attention(kind, d, q, k, v, ld_q, ld_kv, nullptr, o, ld_o, lse, s, g_q, eps);
+  }
+  int rc;
+  if (ld_q == ld_kv && reinterpret_cast<unsigned char *>(k) == reinterpret_cast<unsigned char *>(q) + d.A * 2) {
+    rc = launch_qk_norm_rope(q, ld_q, d.N, 2 * H, H, dh, g_q, g_k, eps, rope, d.S, (int)d.T, s);   // q | k side by side
+  } else {
+    rc = launch_qk_norm_rope(q, ld_q, d.N, H, H, dh, g_q, g_k, eps, rope, d.S, (int)d.T, s);
+    if (rc == DDIT_OK) rc = launch_qk_norm_rope(k, ld_kv, d.N, H, 0, dh, g_q, g_k, eps, rope, d.S, (int)d.T, s);
+  }
+  if (rc != DDIT_OK) return rc;
+  return run_attention(kind, d, q, k, v, ld_q, ld_kv, nullptr, o, ld_o, lse, s);
 }
 
 struct Taps {
@@ -208,14 +244,21 @@ int run_layer(ddit_attn_kind kind, const Dims &d, const ddit_layer_weights &w, c
   base(xh, D, w.w_qkv, w.b_qkv, N, (int)(3 * A), (int)D); g.out = qkv; g.ld_out = 3 * A;
   DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
   {
-    const bool norm = (flags & DDIT_FLAG_QK_NORM) != 0;
-    const bool rope = (flags & DDIT_FLAG_ROPE_TEMPORAL) != 0 && kind == DDIT_ATTN_TEMPORAL;
-    if (norm || rope)
-      DDIT_TRY(launch_qk_norm_rope(qkv, 3 * A, N, (int)d.H, (int)d.dh, norm ? w.g_q : nullptr, norm ? w.g_k : nullptr, eps,
-                                   rope ? reinterpret_cast<const float *>(ws + lo.rope) : nullptr, d.S, (int)d.T, s));
+    // With taps the treated q | k must be visible in memory (the tap shows what the attention reads), so
+    // the treatment then runs as a pass of its own; otherwise it is folded into the attention kernels.
+    const bool norm = (flags & DDIT_FLAG_QK_NORM) != 0, rope = (flags & DDIT_FLAG_ROPE_TEMPORAL) != 0;
+    const void *gq = norm ? w.g_q : nullptr, *gk = norm ? w.g_k : nullptr;
+    const float *tab = rope ? reinterpret_cast<const float *>(ws + lo.rope) : nullptr;
+    if (tp.on) {
+      DDIT_TRY(launch_qk_norm_rope(qkv, 3 * A, N, 2 * (int)d.H, (int)d.H, (int)d.dh, gq, gk, eps,
+                                   kind == DDIT_ATTN_TEMPORAL ? tab : nullptr, d.S, (int)d.T, s));
+      DDIT_TRY(tp.keep(DDIT_TAP_QKV, qkv));
+      DDIT_TRY(run_attention(kind, d, qkv, qkv + A * 2, qkv + 2 * A * 2, 3 * A, 3 * A, nullptr, o, A, nullptr, s));
+    } else {
+      DDIT_TRY(run_self_attention(kind, d, qkv, qkv + A * 2, qkv + 2 * A * 2, 3 * A, 3 * A, gq, gk, eps, tab, true, o, A,
+                                  nullptr, s));
+    }
   }
-  DDIT_TRY(tp.keep(DDIT_TAP_QKV, qkv));
-  DDIT_TRY(run_attention(kind, d, qkv, qkv + A * 2, qkv + 2 * A * 2, 3 * A, 3 * A, nullptr, o, A, nullptr, s));
   DDIT_TRY(tp.keep(DDIT_TAP_O, o));
   base(o, A, w.w_o, w.b_o, N, (int)D, (int)A); gated(2); g.out = xh; g.ld_out = D;   // also xh := bf16(x)
   DDIT_TRY(launch_gemm(DDIT_EPI_RESIDUAL_F32, g, s));
@@ -556,7 +599,30 @@ int ddit_qk_norm_rope_fwd(void *qk, int64_t ld, int64_t N, int32_t H, int32_t dh
   }
   hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
   if (rope_table_or_null) DDIT_TRY(launch_rope_table(rope_table_or_null, T, dh, s));
-  return launch_qk_norm_rope(qk, ld, N, H, dh, g_q, g_k, eps, rope_table_or_null, S, T, s);
+  return launch_qk_norm_rope(qk, ld, N, 2 * H, H, dh, g_q, g_k, eps, rope_table_or_null, S, T, s);
+}
+
+int ddit_self_attn_fwd(ddit_attn_kind kind, const ddit_shape *shape, void *q, void *k, const void *v, int64_t ld_q,
+                       int64_t ld_kv, const void *g_q, const void *g_k, float *rope_table_or_null, int fuse, void *o,
+                       int64_t ld_o, float *lse_or_null, void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  if (kind != DDIT_ATTN_SPATIAL && kind != DDIT_ATTN_TEMPORAL) { set_error("self-attention kind must be spatial or temporal"); return DDIT_ERR_INVALID_ARG; }
+  if (!q || !k || !v || !o) { set_error("q, k, v and o must not be NULL"); return DDIT_ERR_INVALID_ARG; }
+  if ((g_q == nullptr) != (g_k == nullptr)) { set_error("g_q and g_k must be given together"); return DDIT_ERR_INVALID_ARG; }
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (g_q && (!aligned16(g_q) || !aligned16(g_k))) ||
+      (rope_table_or_null && !aligned16(rope_table_or_null))) {
+    set_error("pointers must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT;
+  }
+  if (ld_q < d.A || ld_kv < d.A || ld_o < d.A) { set_error("leading dimensions must be at least H*dh=%lld", (long long)d.A); return DDIT_ERR_INVALID_ARG; }
+  if (ld_q % 8 || ld_kv % 8 || ld_o % 8) { set_error("leading dimensions must be multiples of 8"); return DDIT_ERR_ALIGNMENT; }
+  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
+  const float *tab = nullptr;
+  if (rope_table_or_null && kind == DDIT_ATTN_TEMPORAL) {
+    DDIT_TRY(launch_rope_table(rope_table_or_null, (int)d.T, (int)d.dh, s));
+    tab = rope_table_or_null;
+  }
+  return run_self_attention(kind, d, q, k, v, ld_q, ld_kv, g_q, g_k, shape->ln_eps, tab, fuse != 0, o, ld_o, lse_or_null, s);
 }
 
 int ddit_linear_tile_count(void) { return gemm_tile_count(); }

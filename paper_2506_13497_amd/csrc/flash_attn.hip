@@ -81,6 +81,8 @@ struct FlashParams {
   float scale_log2;  // log2(e) / sqrt(dh)
   float scale;       // 1 / sqrt(dh)
   float rebase;      // 8 / scale_log2: a score this far above its query's reference moves the reference
+  const bf16_t *q_norm_g;   // per-head RMS-norm scales of the queries [dh], or null
+  float q_norm_eps;
 };
 
 template <int DH>
@@ -193,6 +195,26 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_attn(FlashParams p) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) qf[ks][e] = (bf16_t)0.f;
       if (d0 < DH) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + d0);
+    }
+    if (p.q_norm_g) {
+      // per-head RMS normalisation of the query on its way in: lanes l and l ^ 32 hold the two halves
+      // of every 16 elements of one query; fp32 arithmetic, one rounding back to bf16
+      float ss = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < C::KS; ++ks)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += (float)qf[ks][e] * (float)qf[ks][e];   // columns past the head dim are zero
+      ss += __shfl_xor(ss, 32, 64);
+      const float rinv = rsqrtf(ss * (1.0f / DH) + p.q_norm_eps);
+#pragma unroll
+      for (int ks = 0; ks < C::KS; ++ks) {
+        const int d0 = 16 * ks + 8 * lh;
+        if (d0 < DH) {
+          const bf16x8 g = *reinterpret_cast<const bf16x8 *>(p.q_norm_g + d0);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) qf[ks][e] = (bf16_t)((float)qf[ks][e] * rinv * (float)g[e]);
+        }
+      }
     }
   };
   load_q(qtile * QT + wave * 32);
@@ -639,6 +661,8 @@ int launch_flash_attn(const AttnArgs &a, hipStream_t s) {
   p.scale = 1.0f / sqrtf((float)a.dh);
   p.scale_log2 = p.scale * 1.4426950408889634f;
   p.rebase = 8.0f / p.scale_log2;
+  p.q_norm_g = reinterpret_cast<const bf16_t *>(a.q_norm_g);
+  p.q_norm_eps = a.q_norm_eps;
   if ((int64_t)a.n_groups * a.H > 0x3fffffff) {
     set_error("attention grid too large (groups=%d heads=%d)", a.n_groups, a.H);
     return -2;

@@ -34,11 +34,11 @@ __global__ void k_rope_table(float2 *__restrict__ tab, int T, int half) {
 }
 
 struct QkArgs {
-  bf16_t *qk;              // first q column of token 0
+  bf16_t *qk;              // first treated column of token 0
   int64_t ld;              // row stride in elements
   int64_t pieces;          // N * pieces_per_token
-  int pieces_per_token;    // 2 * H * (DH / 8)
-  int H;
+  int pieces_per_token;    // slots * (DH / 8), slots = heads treated per token (q heads first, then k heads)
+  int q_slots;             // the first q_slots heads take g_q, the rest g_k
   const bf16_t *g_q, *g_k; // [DH] or null: no normalisation
   float eps;
   const float2 *rope;      // [T, DH/2] or null: no rotation
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(BLOCK) void k_qk_norm_rope(QkArgs a) {
   const bool live = f < a.pieces;
   const int64_t n = live ? f / a.pieces_per_token : 0;
   const int r = live ? (int)(f - n * a.pieces_per_token) : 0;
-  const int slot = r / PIECES, piece = r - slot * PIECES;   // slot < H: a q head, else a k head
+  const int slot = r / PIECES, piece = r - slot * PIECES;   // slot < q_slots: a q head, else a k head
   float v[8];
   uint4 raw = make_uint4(0, 0, 0, 0);
   bf16_t *ptr = a.qk + n * a.ld + (int64_t)r * 8;
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(BLOCK) void k_qk_norm_rope(QkArgs a) {
 #pragma unroll
     for (int j = 0; j < PIECES; ++j) tot += part[g0 + j];
     const float rinv = rsqrtf(tot * (1.0f / DH) + a.eps);
-    const uint4 graw = *reinterpret_cast<const uint4 *>((slot < a.H ? a.g_q : a.g_k) + piece * 8);
+    const uint4 graw = *reinterpret_cast<const uint4 *>((slot < a.q_slots ? a.g_q : a.g_k) + piece * 8);
     const unsigned gw[4] = {graw.x, graw.y, graw.z, graw.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -124,14 +124,14 @@ int launch_rope_table(float *table, int T, int dh, hipStream_t s) {
   return hip_fail(hipGetLastError(), "rope table launch");
 }
 
-int launch_qk_norm_rope(void *qk, int64_t ld, int64_t N, int H, int dh, const void *g_q, const void *g_k, float eps,
-                        const float *rope_table, int64_t S, int T, hipStream_t s) {
-  if (N == 0 || (!g_q && !rope_table)) return 0;
+int launch_qk_norm_rope(void *qk, int64_t ld, int64_t N, int slots, int q_slots, int dh, const void *g_q,
+                        const void *g_k, float eps, const float *rope_table, int64_t S, int T, hipStream_t s) {
+  if (N == 0 || slots == 0 || (!g_q && !rope_table)) return 0;
   QkArgs a;
   a.qk = reinterpret_cast<bf16_t *>(qk); a.ld = ld;
-  a.pieces_per_token = 2 * H * (dh / 8);
+  a.pieces_per_token = slots * (dh / 8);
   a.pieces = N * a.pieces_per_token;
-  a.H = H;
+  a.q_slots = q_slots;
   a.g_q = reinterpret_cast<const bf16_t *>(g_q); a.g_k = reinterpret_cast<const bf16_t *>(g_k);
   a.eps = eps;
   a.rope = reinterpret_cast<const float2 *>(rope_table);

@@ -30,6 +30,10 @@ struct TemporalParams {
   int n_hg;            // head groups per location
   float scale_log2;    // log2(e) / sqrt(dh)
   float scale;         // 1 / sqrt(dh)
+  // optional treatment of q and k on their way in (OPTS form of the kernel):
+  const bf16_t *g_q, *g_k;   // per-head RMS-norm scales [dh], or null
+  const float2 *rope;        // (cos, sin) of frame t, pair i at [t * dh/2 + i], or null
+  float norm_eps;
 };
 
 template <int DH>
@@ -45,10 +49,15 @@ struct TCfg {
 
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int DH>
+// OPTS: q and k are RMS-normalised per head and rotated by their frame's angles after they have
+// landed in LDS (every sequence is loaded exactly once here, so this costs no memory traffic):
+// one thread per (operand, frame, head) row, two passes over its d_h elements, fp32 arithmetic,
+// one rounding back to bf16; scales and the (cos, sin) rows of the T frames sit in LDS beside the operands.
+template <int DH, bool OPTS>
 __global__ __launch_bounds__(256) void k_temporal_attn(TemporalParams p) {
   using C = TCfg<DH>;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[3 * C::MAT];
+  constexpr int OPT_BYTES = OPTS ? TP * (DH / 2) * 8 + 2 * DH * 4 : 0;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[3 * C::MAT + OPT_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, lh = lane >> 5;
 
@@ -90,6 +99,51 @@ __global__ __launch_bounds__(256) void k_temporal_attn(TemporalParams p) {
     for (int m = tid; m < pad_rows * C::RCH; m += 256) {
       const int r = p.T + m / C::RCH, ch = m % C::RCH;
       *reinterpret_cast<uint4 *>(smem + 2 * C::MAT + r * C::PITCH + ch * 16) = make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+  if constexpr (OPTS) {
+    float2 *tab = reinterpret_cast<float2 *>(smem + 3 * C::MAT);
+    float *gs = reinterpret_cast<float *>(smem + 3 * C::MAT + TP * (DH / 2) * 8);
+    if (p.rope)
+      for (int m = tid; m < p.T * (DH / 2); m += 256) tab[m] = p.rope[m];
+    if (tid < 2 * DH) gs[tid] = p.g_q ? (float)(tid < DH ? p.g_q[tid] : p.g_k[tid - DH]) : 1.0f;
+    wg_barrier();
+    // row (operand, frame, head) -> thread; T <= 32 and four heads: at most 256 rows
+    const int hh = tid & 3, r = (tid >> 2) % TP, mat = tid / (4 * TP);
+    if (mat < 2 && r < p.T && hh < nh) {
+      unsigned char *row = smem + mat * C::MAT + r * C::PITCH + hh * (DH * 2);
+      float rinv = 1.0f;
+      if (p.g_q) {
+        float ss = 0.f;
+#pragma unroll
+        for (int c = 0; c < C::DCH; ++c) {
+          const bf16x8 v = *reinterpret_cast<const bf16x8 *>(row + c * 16);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) ss += (float)v[e] * (float)v[e];
+        }
+        rinv = rsqrtf(ss * (1.0f / DH) + p.norm_eps);
+      }
+      const float *g = gs + mat * DH;
+      const float2 *cs = tab + r * (DH / 2);
+#pragma unroll
+      for (int c = 0; c < C::DCH; ++c) {
+        bf16x8 v = *reinterpret_cast<const bf16x8 *>(row + c * 16);
+        float f[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = (float)v[e] * rinv * g[c * 8 + e];
+        if (p.rope) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float2 a = cs[c * 4 + j];
+            const float x0 = f[2 * j], x1 = f[2 * j + 1];
+            f[2 * j] = x0 * a.x - x1 * a.y;
+            f[2 * j + 1] = x1 * a.x + x0 * a.y;
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (bf16_t)f[e];
+        *reinterpret_cast<bf16x8 *>(row + c * 16) = v;
+      }
     }
   }
   wg_barrier();
@@ -196,10 +250,12 @@ __global__ __launch_bounds__(256) void k_temporal_attn(TemporalParams p) {
 
 template <int DH>
 int launch_t(const TemporalParams &p, hipStream_t s) {
+  const bool opts = p.g_q != nullptr || p.rope != nullptr;
   const int64_t locs = (int64_t)p.B * p.S;
   const int64_t blocks = ((locs + 7) / 8) * p.n_hg * 8;
   if (blocks > 0x7fffffff) { ddit::set_error("temporal attention: too many workgroups"); return -2; }
-  hipLaunchKernelGGL(k_temporal_attn<DH>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+  if (opts) hipLaunchKernelGGL((k_temporal_attn<DH, true>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((k_temporal_attn<DH, false>), dim3((unsigned)blocks), dim3(256), 0, s, p);
   return ddit::hip_fail(hipGetLastError(), "temporal attention launch");
 }
 
@@ -210,7 +266,8 @@ namespace ddit {
 int temporal_attn_max_T() { return TP; }
 
 int launch_temporal_attn(const void *q, const void *k, const void *v, void *o, float *lse, int64_t ld_q,
-                         int64_t ld_kv, int64_t ld_o, int B, int T, int S, int H, int dh, hipStream_t s) {
+                         int64_t ld_kv, int64_t ld_o, int B, int T, int S, int H, int dh, const void *g_q,
+                         const void *g_k, float norm_eps, const float *rope_table, hipStream_t s) {
   if (B == 0 || S == 0 || T == 0) return 0;
   if (T > TP) { set_error("temporal attention kernel: T=%d exceeds %d", T, TP); return -2; }
   TemporalParams p;
@@ -224,6 +281,10 @@ int launch_temporal_attn(const void *q, const void *k, const void *v, void *o, f
   p.n_hg = (H + HG - 1) / HG;
   p.scale = 1.0f / sqrtf((float)dh);
   p.scale_log2 = p.scale * 1.4426950408889634f;
+  p.g_q = reinterpret_cast<const bf16_t *>(g_q);
+  p.g_k = reinterpret_cast<const bf16_t *>(g_k);
+  p.rope = reinterpret_cast<const float2 *>(rope_table);
+  p.norm_eps = norm_eps;
   if (dh == 72) return launch_t<72>(p, s);
   if (dh == 64) return launch_t<64>(p, s);
   set_error("dh=%d: supported head dims are 64 and 72", dh);

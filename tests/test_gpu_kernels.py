@@ -298,6 +298,54 @@ def test_cross_attention_batch2_masks(lib):
     _attn_case(lib, "cross", sh, valid=[45, 290], Lq=200)
 
 
+# ---- self-attention with q/k normalisation and rotary embedding folded into the attention kernels
+OPT_SHAPES = [
+    syn.Shape(1, 4, 8, 8, 256, 4, 64, 1024, 16, 1),       # one key tile, dh 64
+    syn.Shape(2, 3, 15, 27, 1152, 3, 72, 4608, 300, 1),   # S = 405 ragged, three heads (a partial head group), batch 2
+    syn.Shape(1, 30, 9, 16, 1152, 16, 72, 4608, 300, 1),  # T = 30 frames, 16 heads
+    syn.Shape(1, 40, 3, 5, 144, 2, 72, 64, 8, 1),         # T = 40: beyond the dedicated temporal kernel
+]
+
+
+@pytest.mark.parametrize("sh", OPT_SHAPES, ids=lambda s: "B%dT%dS%dH%ddh%d" % (s.B, s.T, s.S, s.H, s.dh))
+@pytest.mark.parametrize("kind", ["spatial", "temporal"])
+@pytest.mark.parametrize("norm,rope", [(True, False), (False, True), (True, True)], ids=["norm", "rope", "norm+rope"])
+@pytest.mark.parametrize("fuse,one_buffer", [(True, True), (True, False), (False, True), (False, False)],
+                         ids=["fused-qkvbuf", "fused-separate", "passes-qkvbuf", "passes-separate"])
+def test_self_attention_with_options(lib, sh, kind, norm, rope, fuse, one_buffer):
+    if kind == "spatial" and sh.S > 200 and sh.T > 8:
+        pytest.skip("covered by the smaller frames")
+    d = syn.make_attn_inputs(kind, sh, 70, q_scale=1.0)
+    q, k, v = (to_f64(d[n]) for n in "qkv")                       # [B,T,S,H,dh]
+    A, dh = sh.A, sh.dh
+    gq = syn.f32_to_bf16_bits((1 + 0.2 * np.random.default_rng(11).standard_normal(dh)).astype(np.float32))
+    gk = syn.f32_to_bf16_bits((1 + 0.2 * np.random.default_rng(12).standard_normal(dh)).astype(np.float32))
+    qq, kk = q, k
+    if norm:
+        qq, kk = ora.rms_norm(qq, to_f64(gq)), ora.rms_norm(kk, to_f64(gk))
+    if rope and kind == "temporal":
+        frame = np.arange(sh.T, dtype=np.float64)[None, :, None, None]
+        qq, kk = ora.rotary(qq, frame), ora.rotary(kk, frame)
+    o_ref, lse_ref = (ora.spatial_attention if kind == "spatial" else ora.temporal_attention)(qq, kk, v)
+    dq, dk, dv = (to_dev(d[n]).reshape(-1, A) for n in "qkv")
+    ld = A
+    if one_buffer:
+        buf = torch.cat([dq, dk, dv], dim=1).contiguous()
+        dq, dk, dv = buf[:, :A], buf[:, A:2 * A], buf[:, 2 * A:]
+        ld = 3 * A
+    v_before = dv.clone()
+    o = torch.full((sh.N, A), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.full(lse_ref.shape, float("nan"), dtype=torch.float32, device="cuda")
+    tab = torch.empty(sh.T * dh, dtype=torch.float32, device="cuda") if rope else None
+    kid = lib.DDIT_ATTN_SPATIAL if kind == "spatial" else lib.DDIT_ATTN_TEMPORAL
+    lib.ddit_self_attn_fwd(kid, _shape(lib, sh), dq, dk, dv, ld, ld, to_dev(gq) if norm else None, to_dev(gk) if norm else None,
+                           tab, fuse, o, A, lse)
+    torch.cuda.synchronize()
+    assert_parity(dev_to_f64(o).reshape(o_ref.shape), o_ref, "%s attention with options" % kind)
+    assert np.max(np.abs(dev_to_f64(lse) - lse_ref)) < 3e-2, "lse"
+    assert torch.equal(dv, v_before), "v was written"
+
+
 # Short text sequences shared by many queries take the resident form of the kernel (all K/V tiles of a
 # (sample, head) unit fetched once, the workgroup walking over a run of query tiles): it is chosen when a
 # unit has at least four 256-query tiles per workgroup, at one workgroup per CU.  These shapes reach it on
