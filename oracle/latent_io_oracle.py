@@ -100,16 +100,17 @@ def output_head(x, temb, final_table, w_final, b_final, Hp, Wp, C_out):
     return unpatchify(so.linear(xh, w_final, b_final), Hp, Wp, C_out)
 
 
-def eps_theta(z, c_text, valid_len, t, io_w, sw, blocks, H, dh):
+def eps_theta(z, c_text, valid_len, t, io_w, sw, blocks, H, dh, rope_temporal=False):
     """The whole model: latent z [B,C,T,2Hp,2Wp], text c_text [B,Ly,C_text], timesteps t [B]
     -> prediction with the latent's shape.  io_w: dict w_patch,b_patch,w_y1,b_y1,w_y2,b_y2,
-    final_table,w_final,b_final; sw, blocks as in stdit_oracle.denoise_step."""
+    final_table,w_final,b_final; sw, blocks and the two self-attention options as in
+    stdit_oracle.denoise_step."""
     D = io_w["w_patch"].shape[0]
     B, C, T, Hl, Wl = z.shape
     x = embed_latent(z, io_w["w_patch"], io_w["b_patch"], D)
     y = embed_caption(c_text, io_w["w_y1"], io_w["b_y1"], io_w["w_y2"], io_w["b_y2"])
     temb = so.timestep_embedding(t, sw)
-    x = so.denoise_step(x, y, valid_len, t, sw, blocks, H, dh, temb=temb)
+    x = so.denoise_step(x, y, valid_len, t, sw, blocks, H, dh, temb=temb, rope_temporal=rope_temporal)
     C_out = io_w["w_final"].shape[0] // 4
     return output_head(x, temb, io_w["final_table"], io_w["w_final"], io_w["b_final"], Hl // 2, Wl // 2, C_out)
 

@@ -32,17 +32,17 @@ def lib():
     return m
 
 
-def _shape(lib, sh):
-    return lib.make_shape(sh.B, sh.T, sh.Hp, sh.Wp, sh.D, sh.H, sh.dh, sh.M, sh.Ly, sh.n_blocks)
+def _shape(lib, sh, flags=0):
+    return lib.make_shape(sh.B, sh.T, sh.Hp, sh.Wp, sh.D, sh.H, sh.dh, sh.M, sh.Ly, sh.n_blocks, flags)
 
 
 class Setup:
-    def __init__(self, lib, sh, C, C_text, base=31):
-        self.sh, self.C, self.C_text = sh, C, C_text
-        self.shape = _shape(lib, sh)
+    def __init__(self, lib, sh, C, C_text, base=31, options=False):
+        self.sh, self.C, self.C_text, self.options = sh, C, C_text, options
+        self.shape = _shape(lib, sh, (lib.DDIT_FLAG_QK_NORM | lib.DDIT_FLAG_ROPE_TEMPORAL) if options else 0)
         self.io_w = syn.make_io_weights(sh, base, C, C_text, C)
         self.sw = syn.make_step_weights(sh, base)
-        self.blocks = [syn.make_block_weights(sh, base, i, table_std=0.3) for i in range(sh.n_blocks)]
+        self.blocks = [syn.make_block_weights(sh, base, i, qk_norm=options, table_std=0.3) for i in range(sh.n_blocks)]
         self.z = syn.make_latent(sh, base, C)
         self.c_text = syn.make_caption(sh, base, C_text)
         self.c_unc = syn.make_caption(sh, base, C_text, which=1)
@@ -61,7 +61,8 @@ class Setup:
 
     def oracle_model(self, c_bits, valid):
         c = to_f64(c_bits)
-        return lambda z, t: lio.eps_theta(z, c, valid, t, self.f_io, self.f_sw, self.f_blocks, self.sh.H, self.sh.dh)
+        return lambda z, t: lio.eps_theta(z, c, valid, t, self.f_io, self.f_sw, self.f_blocks, self.sh.H, self.sh.dh,
+                                          rope_temporal=self.options)
 
 
 @pytest.mark.parametrize("case", IO_CASES, ids=IDS)
@@ -111,6 +112,20 @@ def test_eps_theta(lib, case):
     torch.cuda.synchronize()
     ref = st.oracle_model(st.c_text, np.array(valid))(st.z.astype(np.float64), np.array(t))
     assert_parity(dev_to_f64(out), ref, "eps_theta on a latent")
+
+
+def test_eps_theta_with_qk_norm_and_rotary(lib):
+    """Latent in, prediction out with both self-attention options on (the folded paths of the step)."""
+    st = Setup(lib, *IO_CASES[0], options=True)
+    sh = st.sh
+    valid = [sh.Ly - 3 * b for b in range(sh.B)]
+    t = [100.0 + 700.0 * b for b in range(sh.B)]
+    y = st.caption_dev(lib, st.c_text)
+    out = torch.full((sh.B, st.C, sh.T, 2 * sh.Hp, 2 * sh.Wp), float("nan"), dtype=torch.float32, device="cuda")
+    lib.ddit_eps_theta(st.shape, st.step, st.io, to_dev(st.z), y, valid, t, out, st.ws)
+    torch.cuda.synchronize()
+    ref = st.oracle_model(st.c_text, np.array(valid))(st.z.astype(np.float64), np.array(t))
+    assert_parity(dev_to_f64(out), ref, "eps_theta with q/k normalisation and rotary embedding")
 
 
 def test_solver_step(lib):
