@@ -299,6 +299,10 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TN][TM], unsigned 
           int64_t smp = my_sample0 + 1, t = sample1_tok + p.tokens_per_sample;
           const int64_t tk = tok < p.N ? tok : p.N - 1;
           while (t <= tk) { ++smp; t += p.tokens_per_sample; }
+          // rows past the end of a problem that ends inside the tile's first sample would name a
+          // sample that does not exist (their result is never stored, but the read must stay inside c6)
+          const int64_t last = (p.N - 1) / p.tokens_per_sample;
+          if (smp > last) smp = last;
           gfar = p.gate_c6 + smp * p.gate_c6_stride;
         }
 #pragma unroll
