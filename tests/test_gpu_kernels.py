@@ -163,6 +163,31 @@ def test_linear_every_tile(lib, tile, epi, N, n, k):
     _check_linear(lib, N, n, k, epi, tile)
 
 
+@pytest.mark.parametrize("tile", range(N_TILES))
+@pytest.mark.parametrize("N,tps", [(50, 7), (7, 7), (1, 1), (200, 3)])
+def test_linear_residual_tile_over_many_samples(lib, tile, N, tps):
+    """Samples much shorter than a tile: every row looks up its own sample's gate; the rows of the tile
+    past the end of the problem must not name a sample that does not exist."""
+    n, k = 264, 96
+    B = (N + tps - 1) // tps
+    u = syn.normal_bits((41, N, tps), (N, k), 1.0)
+    W = syn.normal_bits((42, N, tps), (n, k), 1.0 / math.sqrt(k))
+    b = syn.normal_bits((43, N, tps), (n,), 0.5)
+    rng = np.random.default_rng(N + tps)
+    resid = rng.standard_normal((N, n)).astype(np.float32)
+    tab = rng.standard_normal((6, n)).astype(np.float32)
+    c6 = rng.standard_normal((B, 6 * n)).astype(np.float32)
+    dres = to_dev(resid)
+    lib.ddit_linear_fwd_tile(tile, 2, to_dev(u), k, to_dev(W), to_dev(b), N, n, k, None, 0, resid=dres, ada_table=to_dev(tab),
+                             c6=to_dev(c6), gate_row=5, tokens_per_sample=tps)
+    torch.cuda.synchronize()
+    lin = ora.linear(to_f64(u), to_f64(W), to_f64(b))
+    ref = resid.astype(np.float64)
+    for r in range(N):
+        ref[r] += (tab[5] + c6[r // tps].reshape(6, n)[5]).astype(np.float64) * lin[r]
+    assert_parity(dev_to_f64(dres), ref, "residual linear, %d samples in a tile" % B)
+
+
 def _check_linear(lib, N, n, k, epi, tile):
     u = syn.normal_bits((11, N, n, k), (N, k), 1.0)
     W = syn.normal_bits((12, N, n, k), (n, k), 1.0 / math.sqrt(k))
