@@ -118,3 +118,50 @@ def test_attention_random_shapes(lib, seed):
         lib.ddit_attn_fwd(kid, shape, to_dev(d["q"]), to_dev(d["k"]), to_dev(d["v"]), A, A, c["valid"], o, A)
         torch.cuda.synchronize()
         assert_parity(dev_to_f64(o), ref, "seed %d case %s" % (seed, {n: c[n] for n in c if n != "valid"}))
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_layernorm_and_qk_treatment_random_shapes(lib, seed):
+    rng = random.Random(50 + seed)
+    for i in range(16):          # modulated LayerNorm: any hidden size that is a multiple of 8, samples of any length
+        N, D = rng.choice([1, 3, 4, 5, 17, 64, 255, 1000]), 8 * rng.randrange(1, 513)
+        tps = rng.choice([N, max(1, N // 2), max(1, N // 7)])
+        B = (N + tps - 1) // tps
+        g = np.random.default_rng(seed * 100 + i)
+        x = (g.standard_normal((N, D)) * 1.5 + 0.3).astype(np.float32)
+        tab = (g.standard_normal((6, D)) * 0.5).astype(np.float32)
+        c6 = (g.standard_normal((B, 6 * D)) * 0.5).astype(np.float32)
+        which = rng.randrange(2)
+        out = torch.full((N, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lib.ddit_modulated_layernorm_fwd(to_dev(x), to_dev(tab), to_dev(c6), which, tps, 1e-6, out)
+        torch.cuda.synchronize()
+        xn = ora.layer_norm(x.astype(np.float64))
+        ref = np.empty((N, D))
+        sfx = "msa" if which == 0 else "mlp"
+        for r in range(N):
+            m = ora.split_modulation(tab.astype(np.float64), c6[r // tps].astype(np.float64), D)
+            ref[r] = ora.modulate(xn[r], m["shift_" + sfx], m["scale_" + sfx])
+        assert_parity(dev_to_f64(out), ref, "LayerNorm N=%d D=%d tps=%d which=%d" % (N, D, tps, which))
+    for i in range(16):          # q | k treatment in place: any head count, both head dims, padded rows
+        N, H, dh = rng.choice([1, 2, 9, 63, 64, 65, 577, 1000]), rng.randrange(1, 17), rng.choice([64, 72])
+        S, T = rng.randrange(1, 40), rng.randrange(1, 50)
+        A = H * dh
+        ld = 3 * A + 8 * rng.randrange(0, 3)
+        norm, rope = rng.choice([(True, False), (False, True), (True, True)])
+        buf = syn.normal_bits((70 + seed, i), (N, ld), 1.5)
+        gq = syn.f32_to_bf16_bits((1 + 0.2 * np.random.default_rng(i).standard_normal(dh)).astype(np.float32))
+        gk = syn.f32_to_bf16_bits((1 + 0.2 * np.random.default_rng(100 + i).standard_normal(dh)).astype(np.float32))
+        d = to_dev(buf)
+        tab = torch.empty(T * dh, dtype=torch.float32, device="cuda") if rope else None
+        lib.ddit_qk_norm_rope_fwd(d, ld, N, H, dh, to_dev(gq) if norm else None, to_dev(gk) if norm else None, 1e-6, S, T, tab)
+        torch.cuda.synchronize()
+        got, x = dev_to_f64(d), to_f64(buf)
+        frame = ((np.arange(N) // S) % T).astype(np.float64)[:, None]
+        for j, gg in enumerate((gq, gk)):
+            u = x[:, j * A:(j + 1) * A].reshape(N, H, dh)
+            if norm:
+                u = ora.rms_norm(u, to_f64(gg), 1e-6)
+            if rope:
+                u = ora.rotary(u, frame)
+            assert_parity(got[:, j * A:(j + 1) * A], u.reshape(N, A), "q/k treatment N=%d H=%d dh=%d S=%d T=%d" % (N, H, dh, S, T))
+        assert np.array_equal(got[:, 2 * A:], x[:, 2 * A:]), "columns past q | k were touched"
