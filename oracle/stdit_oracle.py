@@ -19,7 +19,7 @@ Where the paper is silent (it never writes the block down), the readings are:
     added to the residual stream; a *block* = spatial layer then temporal layer;
     "28 blocks" = 56 layers (this structure counts 1.19 B parameters, matching
     Table 1's 1.1 B; the alternative with one cross-attention and one MLP per block
-    counts 0.74 B);
+    counts 0.75 B);
   * adaLN-single: one conditioning vector c6 = W_ada SiLU(temb) + b_ada per sample,
     shared by all layers, plus a learned per-layer table [6,D]; their sum splits into
     (shift_msa, scale_msa, gate_msa, shift_mlp, scale_mlp, gate_mlp);

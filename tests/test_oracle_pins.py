@@ -20,6 +20,18 @@ from oracle import stdit_oracle as ora
 TINY = syn.Shape(B=2, T=3, Hp=2, Wp=2, D=16, H=2, dh=4, M=24, Ly=5, n_blocks=2)
 
 
+def _paper_values():
+    """The few numbers the paper itself prints (tests/golden/paper_printed_values.txt)."""
+    import os
+    out = {}
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_printed_values.txt")):
+        line = line.split("#", 1)[0].strip()
+        if line:
+            k, v = (t.strip() for t in line.split("=", 1))
+            out[k] = float(v)
+    return out
+
+
 def _rand(shape, seed, scale=1.0):
     return np.random.default_rng(seed).standard_normal(shape) * scale
 
@@ -383,7 +395,14 @@ class TestStep:
     def test_parameter_count_matches_table_1(self):  # P12
         n = ora.parameter_count(1152, 1152, 4608, 28)
         assert abs(n - 1.19e9) < 0.01e9           # 1.19 B for this structure
-        assert abs(n / 1.1e9 - 1.0) < 0.10        # Table 1: STDiT3, 1.1 B
+        printed = _paper_values()["stdit3_parameters_billion"] * 1e9      # Table 1: STDiT3, 1.1 B
+        assert printed == 1.1e9 and abs(n / printed - 1.0) < 0.10
+        # the alternative reading (one cross-attention and one MLP per block) is far from what the table prints
+        D, A, M = 1152, 1152, 4608
+        cross = (A * D + A) + (2 * A * D + 2 * A) + (D * A + D)
+        mlp = (M * D + M) + (D * M + D)
+        one_per_block = n - 28 * (cross + mlp)
+        assert abs(one_per_block - 0.75e9) < 0.01e9 and abs(one_per_block / printed - 1.0) > 0.25
         # count equals the number of elements the generator actually makes
         sh = syn.CONFIGS["C2"]["shape"]
         per_layer = sum(int(np.prod(s)) for s in syn.layer_shapes(sh).values())
