@@ -52,6 +52,10 @@ struct GemmArgs {
   int tile;                         // index into the tile list, or negative: the launcher's own choice
 };
 int launch_gemm(int epilogue, const GemmArgs &a, hipStream_t s);
+// G problems that share u (a.W, a.bias, a.out are ignored; a.n is one problem's out-features): 0 = launched,
+// 1 = this shape cannot be grouped (nothing launched: launch them one by one), negative = error
+int launch_gemm_grouped(const GemmArgs &a, int G, const void *const *W, const void *const *bias, void *const *out,
+                        hipStream_t s);
 int gemm_tile_count();
 int gemm_tile_info(int tile, int *rows, int *cols, int *wavefronts, int *wg_per_cu);
 // the tile the launcher would take (cus <= 0: the current device's CU count); us_per_tile, if not

@@ -43,7 +43,7 @@ inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 struct Dims {
-  int64_t B, T, S, L, N, D, H, dh, A, M, Ly;
+  int64_t B, T, S, L, N, D, H, dh, A, M, Ly, n_blocks;
 };
 
 struct Layout {
@@ -71,7 +71,7 @@ int check_shape(const ddit_shape *sh, Dims *d) {
   if (sh->D % 8 || sh->M % 8) { set_error("D=%d and M=%d must be multiples of 8", sh->D, sh->M); return DDIT_ERR_UNSUPPORTED; }
   if (sh->D > 4096) { set_error("D=%d: hidden size above 4096 is not supported", sh->D); return DDIT_ERR_UNSUPPORTED; }
   d->B = sh->B; d->T = sh->T; d->S = (int64_t)sh->Hp * sh->Wp; d->L = d->T * d->S; d->N = d->B * d->L;
-  d->D = sh->D; d->H = sh->H; d->dh = sh->dh; d->A = A; d->M = sh->M; d->Ly = sh->Ly;
+  d->D = sh->D; d->H = sh->H; d->dh = sh->dh; d->A = A; d->M = sh->M; d->Ly = sh->Ly; d->n_blocks = sh->n_blocks;
   if (d->N > (int64_t)1 << 30) { set_error("B*T*S=%lld tokens: too many", (long long)d->N); return DDIT_ERR_UNSUPPORTED; }
   return DDIT_OK;
 }
@@ -83,7 +83,8 @@ void make_layout(const Dims &d, uint32_t flags, Layout *lo) {
   lo->xh = take((size_t)d.N * d.D * 2);
   lo->qkv = take((size_t)d.N * 3 * d.A * 2);
   lo->o = take((size_t)d.N * d.A * 2);
-  lo->kvc = take((size_t)d.B * d.Ly * 2 * d.A * 2);
+  // text k|v of every layer of a step (one layer's worth at least: the single-block call uses it layer by layer)
+  lo->kvc = take((size_t)(d.n_blocks > 0 ? 2 * d.n_blocks : 1) * d.B * d.Ly * 2 * d.A * 2);
   lo->h = take((size_t)d.N * d.M * 2);
   lo->c6 = take((size_t)d.B * 6 * d.D * 4);
   lo->cond = take((size_t)d.B * (256 + 2 * d.D) * 4);
@@ -294,6 +295,38 @@ int run_layer(ddit_attn_kind kind, const Dims &d, const ddit_layer_weights &w, c
   return DDIT_OK;
 }
 
+// Text k|v projections of all 2 * n_blocks layers: y [B*Ly, D] against every layer's w_ckv, layer l's result at
+// out + l * (B*Ly*2A*2 bytes).  One grouped launch where the shape allows it (the projections share y and are
+// far too small, one by one, for the chip), else layer by layer.
+int project_text_kv(const Dims &d, const ddit_step_weights *weights, const void *y, unsigned char *out, hipStream_t s) {
+  const size_t per_layer = (size_t)d.B * d.Ly * 2 * d.A * 2;
+  const int layers = (int)(2 * d.n_blocks);
+  GemmArgs g;
+  memset(&g, 0, sizeof(g)); g.tile = -1;
+  g.u = y; g.ld_u = d.D; g.N = d.B * d.Ly; g.n = (int)(2 * d.A); g.k = (int)d.D; g.ld_out = 2 * d.A; g.tokens_per_sample = d.Ly;
+  constexpr int CHUNK = 128;
+  for (int l0 = 0; l0 < layers; l0 += CHUNK) {
+    const int G = layers - l0 < CHUNK ? layers - l0 : CHUNK;
+    const void *W[CHUNK], *bias[CHUNK];
+    void *o[CHUNK];
+    for (int j = 0; j < G; ++j) {
+      const int l = l0 + j;
+      const ddit_layer_weights &w = (l & 1) ? weights->blocks[l >> 1].temporal : weights->blocks[l >> 1].spatial;
+      W[j] = w.w_ckv; bias[j] = w.b_ckv; o[j] = out + (size_t)l * per_layer;
+    }
+    int rc = launch_gemm_grouped(g, G, W, bias, o, s);
+    if (rc == 1) {
+      for (int j = 0; j < G; ++j) {
+        g.W = W[j]; g.bias = bias[j]; g.out = o[j];
+        DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
+      }
+    } else if (rc != 0) {
+      return rc;
+    }
+  }
+  return DDIT_OK;
+}
+
 int check_common(const Dims &d, const Layout &lo, const void *x_in, const void *y, const void *x_out, void *ws,
                  size_t ws_bytes) {
   if (!x_in || !y || !x_out) { set_error("x_in, y and x_out must not be NULL"); return DDIT_ERR_INVALID_ARG; }
@@ -499,21 +532,7 @@ int ddit_cross_kv_precompute(const ddit_shape *shape, const ddit_step_weights *w
       if (!w->w_ckv) { set_error("block %d: w_ckv is NULL", i); return DDIT_ERR_INVALID_ARG; }
       if (!aligned16(w->w_ckv) || (w->b_ckv && !aligned16(w->b_ckv))) { set_error("block %d: w_ckv/b_ckv not 16-byte aligned", i); return DDIT_ERR_ALIGNMENT; }
     }
-  hipStream_t s = reinterpret_cast<hipStream_t>(hip_stream);
-  const size_t per_layer = (size_t)d.B * d.Ly * 2 * d.A * 2;
-  unsigned char *out = reinterpret_cast<unsigned char *>(cross_kv_out);
-  for (int i = 0; i < shape->n_blocks; ++i) {
-    int l = 0;
-    for (const ddit_layer_weights *w : {&weights->blocks[i].spatial, &weights->blocks[i].temporal}) {
-      GemmArgs g;
-      memset(&g, 0, sizeof(g)); g.tile = -1;
-      g.u = y; g.ld_u = d.D; g.W = w->w_ckv; g.bias = w->b_ckv; g.N = d.B * d.Ly; g.n = (int)(2 * d.A); g.k = (int)d.D;
-      g.out = out + (size_t)(2 * i + l) * per_layer; g.ld_out = 2 * d.A; g.tokens_per_sample = d.Ly;
-      DDIT_TRY(launch_gemm(DDIT_EPI_BF16, g, s));
-      ++l;
-    }
-  }
-  return DDIT_OK;
+  return project_text_kv(d, weights, y, reinterpret_cast<unsigned char *>(cross_kv_out), reinterpret_cast<hipStream_t>(hip_stream));
 }
 
 int ddit_denoise_step(const ddit_shape *shape, const ddit_step_weights *weights, const void *x_in,
@@ -556,6 +575,14 @@ int ddit_denoise_step_cached(const ddit_shape *shape, const ddit_step_weights *w
     DDIT_TRY(launch_rope_table(reinterpret_cast<float *>(ws + lo.rope), (int)d.T, (int)d.dh, s));
   const size_t kv_layer = (size_t)d.B * d.Ly * 2 * d.A * 2;
   const unsigned char *kv = reinterpret_cast<const unsigned char *>(cross_kv_or_null);
+  if (!kv && shape->n_blocks > 0) {
+    // no cache given: the text k|v of every layer are formed here, in one grouped launch, into the workspace
+    for (int i = 0; i < shape->n_blocks; ++i)
+      for (const ddit_layer_weights *w : {&weights->blocks[i].spatial, &weights->blocks[i].temporal})
+        if (!w->w_ckv) { set_error("block %d: w_ckv is NULL", i); return DDIT_ERR_INVALID_ARG; }
+    DDIT_TRY(project_text_kv(d, weights, y, ws + lo.kvc, s));
+    kv = ws + lo.kvc;
+  }
   for (int i = 0; i < shape->n_blocks; ++i) {
     tp.layer = 0;
     DDIT_TRY(run_layer(DDIT_ATTN_SPATIAL, d, weights->blocks[i].spatial, y, kv ? kv + (size_t)(2 * i) * kv_layer : nullptr,

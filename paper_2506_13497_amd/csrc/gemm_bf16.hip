@@ -42,6 +42,7 @@
 #include "ddit_common.hpp"
 
 #include <cmath>
+#include <type_traits>
 
 namespace {
 
@@ -62,6 +63,19 @@ struct GemmParams {
   int64_t tokens_per_sample;
   int tiles_m; int tiles_n; int group_w; int total_tiles; int rounds;
 };
+
+// A grouped launch: one token matrix u against G weight matrices of the same shape [group_n, k], each
+// with its own bias and its own output (the text k|v projections of all layers of a step).  To the
+// tile loop it is one problem with G * group_n out-features; a tile lies inside one group
+// (group_n is a multiple of the tile's columns), whose pointers it takes from this table.
+constexpr int MAX_GROUPS = 128;
+struct GroupTable {
+  int group_n;
+  const bf16_t *W[MAX_GROUPS];
+  const bf16_t *bias[MAX_GROUPS];
+  bf16_t *out[MAX_GROUPS];
+};
+struct NoGroups {};
 
 __device__ __forceinline__ float gelu_tanh_f(float u) {
   // 0.5 u (1 + tanh(z)) == u / (1 + exp(-2 z)),  z = sqrt(2/pi) (u + 0.044715 u^3)
@@ -195,7 +209,7 @@ struct GemmCfg {
 template <class C, int TM, int TN, int EPI>
 __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TN][TM], unsigned char *smem, const float *smem_gate,
                                               const GemmParams &p, int64_t my_row0, int my_col0, int64_t my_sample0,
-                                              int tid, int wm, int wn, int l32, int lh) {
+                                              int tid, int wm, int wn, int l32, int lh, bf16_t *my_out, int my_shift) {
   constexpr int BN = C::BN, NT = C::NT, PR = C::PASS_ROWS;
   const unsigned stage_base = lds_offset(smem);
   const int rl_stage = wm * 32 + l32;   // this lane's row inside a pass
@@ -244,7 +258,7 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TN][TM], unsigned 
           const int rl = idx / CPR, c = idx - rl * CPR;          // rl = 32 * wave-row + row
           const int64_t tok = my_row0 + (rl >> 5) * (TM * 32) + b * 32 + (rl & 31);
           const int f = my_col0 + c * 8;
-          if (tok < p.N && f < p.n) *reinterpret_cast<uintx4 *>(p.out + tok * p.ld_out + f) = piece[j];
+          if (tok < p.N && f < p.n) *reinterpret_cast<uintx4 *>(my_out + tok * p.ld_out + (f - my_shift)) = piece[j];
         }
       }
       lds_barrier();   // staged rows are read by other waves until here
@@ -383,9 +397,11 @@ typedef __attribute__((address_space(1))) const void *gbl_ptr_t;
 template <int NJ_>
 struct LoadCount { static constexpr int value = NJ_; };
 
-template <int WGM, int WGN, int TM, int TN, int NS, int EPI>
-__global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI, class GT>
+__global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p, GT gt) {
   using C = GemmCfg<WGM, WGN, TM, TN, NS>;
+  constexpr bool GROUPED = !std::is_same<GT, NoGroups>::value;
+  static_assert(!GROUPED || EPI != 2, "grouped launches write bf16 outputs");
   constexpr int BM = C::BM, BN = C::BN, STAGE = C::STAGE, NW = C::NW;
   constexpr int NFRAG = TM + TN, NMFMA = TM * TN;
   constexpr int AHEAD = NS - 1;          // k-steps in flight ahead of the one being multiplied
@@ -415,6 +431,11 @@ __global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
   const int ld_chunk = ((lane & 3) ^ ((ld_row >> 2) & 3)) * 8;   // element offset of the global chunk to fetch
   const unsigned bias_lds = lds_offset(smem_bias) + (wn * (TN * 32) + 4 * lh) * 2;
 
+  // W, bias, output and first out-feature of the problem that the tile being FETCHED belongs to
+  const bf16_t *W_tile = p.W, *bias_tile = p.bias;
+  bf16_t *out_tile = p.out;
+  int shift_tile = 0;
+
   // The whole tile loop, compiled per NJ = this wavefront's loads per k-step.
   auto run = [&](auto nj_tag) {
     constexpr int NJ = decltype(nj_tag)::value;
@@ -426,7 +447,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
     const int k0_ = (KT) * BK;                                                                     \
     unsigned char *sb_ = smem + (ST) * STAGE + wave * 1024;                                        \
     _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                               \
-      const bf16_t *src_ = ((wave + NW * j) * 16 < BM ? p.u : p.W) + src_off[j] + k0_;             \
+      const bf16_t *src_ = ((wave + NW * j) * 16 < BM ? p.u : W_tile) + src_off[j] + k0_;          \
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)src_, (lds_ptr_t)(sb_ + j * (NW * 1024)), 16, 0, 0); \
     }                                                                                              \
   } while (0)
@@ -438,7 +459,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
     const bool in_ = k0_ + ld_chunk < p.k;                                                         \
     unsigned char *sb_ = smem + (ST) * STAGE + wave * 1024;                                        \
     _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                               \
-      const bf16_t *src_ = ((wave + NW * j) * 16 < BM ? p.u : p.W) + src_off[j] + k0_;             \
+      const bf16_t *src_ = ((wave + NW * j) * 16 < BM ? p.u : W_tile) + src_off[j] + k0_;          \
       if (!in_) src_ = reinterpret_cast<const bf16_t *>(k_zero_block);                             \
       __builtin_amdgcn_global_load_lds((gbl_ptr_t)src_, (lds_ptr_t)(sb_ + j * (NW * 1024)), 16, 0, 0); \
     }                                                                                              \
@@ -465,6 +486,14 @@ __global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
     // Start of a tile's operand stream: source offsets, the tile's bias (one wavefront fetches it,
     // ahead of everything else, so it has landed when k-step 0 has), k-steps 0 .. AHEAD-1.
     auto begin_tile = [&](int64_t row0, int col0, int first_steps) {
+      int n_lim = p.n;             // out-features of the tile's problem
+      if constexpr (GROUPED) {
+        const int g = col0 / gt.group_n;
+        W_tile = gt.W[g]; bias_tile = gt.bias[g]; out_tile = gt.out[g];
+        shift_tile = g * gt.group_n;
+        n_lim = gt.group_n;
+      }
+      const int lcol0 = col0 - shift_tile;   // the tile's first out-feature inside its problem
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         const int R = (wave + NW * j) * 16 + ld_row;
@@ -473,15 +502,15 @@ __global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
           if (t > p.N - 1) t = p.N - 1;           // overhanging rows re-read the last row; never stored
           src_off[j] = (int)(t * p.ld_u) + ld_chunk;
         } else {
-          int f = col0 + R - BM;
-          if (f > p.n - 1) f = p.n - 1;
+          int f = lcol0 + R - BM;
+          if (f > n_lim - 1) f = n_lim - 1;
           src_off[j] = f * p.k + ld_chunk;
         }
       }
-      if (p.bias && wave == 0 && lane < BN / 8) {
-        int f = col0 + lane * 8;
-        if (f > p.n - 8) f = p.n - 8;             // overhanging features: a valid address, never stored
-        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(p.bias + f), (lds_ptr_t)smem_bias, 16, 0, 0);
+      if (bias_tile && wave == 0 && lane < BN / 8) {
+        int f = lcol0 + lane * 8;
+        if (f > n_lim - 8) f = n_lim - 8;         // overhanging features: a valid address, never stored
+        __builtin_amdgcn_global_load_lds((gbl_ptr_t)(bias_tile + f), (lds_ptr_t)smem_bias, 16, 0, 0);
       }
 #pragma unroll
       for (int s = 0; s < AHEAD; ++s) {
@@ -539,7 +568,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
         uint2 bq[4];
 #pragma unroll
         for (int g = 0; g < 4; ++g) bq[g] = make_uint2(0u, 0u);
-        if (p.bias) lds_read4_b64(bq, bias_lds + a * 64);
+        if (GROUPED ? bias_tile != nullptr : p.bias != nullptr) lds_read4_b64(bq, bias_lds + a * 64);
 #pragma unroll
         for (int b = 0; b < TM; ++b)
 #pragma unroll
@@ -597,6 +626,8 @@ __global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
 
       const int64_t my_row0 = row0;
       const int my_col0 = col0;
+      bf16_t *const my_out = out_tile;
+      const int my_shift = GROUPED ? shift_tile : 0;
       const int next = round + 1 < p.rounds ? tile_sequence_index(p, round + 1) : -1;
       if (next >= 0) {
         decode_tile(p, next, tile_m, tile_n);
@@ -604,7 +635,7 @@ __global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
         col0 = tile_n * BN;
         if (EARLY_FETCH) begin_tile(row0, col0, C::EARLY_STEPS);
       }
-      gemm_epilogue<C, TM, TN, EPI>(acc, smem, smem_gate, p, my_row0, my_col0, sample0, tid, wm, wn, l32, lh);
+      gemm_epilogue<C, TM, TN, EPI>(acc, smem, smem_gate, p, my_row0, my_col0, sample0, tid, wm, wn, l32, lh, my_out, my_shift);
       if (next < 0) break;
       if (EARLY_FETCH) finish_begin(C::EARLY_STEPS);
       else begin_tile(row0, col0, AHEAD);
@@ -624,8 +655,8 @@ __global__ __launch_bounds__(WGM *WGN * 64, 2) void k_gemm_bf16(GemmParams p) {
   }
 }
 
-template <int WGM, int WGN, int TM, int TN, int NS, int EPI>
-int launch_one(const GemmParams &p0, hipStream_t s) {
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI, class GT = NoGroups>
+int launch_one(const GemmParams &p0, hipStream_t s, const GT &gt = GT()) {
   using C = GemmCfg<WGM, WGN, TM, TN, NS>;
   constexpr int LDS_BYTES = C::SMEM + C::EXTRA_BYTES;
   static_assert(LDS_BYTES <= 160 * 1024, "the tile's stages must fit the LDS");
@@ -655,12 +686,12 @@ int launch_one(const GemmParams &p0, hipStream_t s) {
   p.rounds = (int)(((total + 7) / 8 + grid / 8 - 1) / (grid / 8));
   static bool attr_set = false;  // benign race: the attribute is idempotent
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<WGM, WGN, TM, TN, NS, EPI>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_bf16<WGM, WGN, TM, TN, NS, EPI, GT>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e != hipSuccess) return ddit::hip_fail(e, "gemm hipFuncSetAttribute");
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_gemm_bf16<WGM, WGN, TM, TN, NS, EPI>), dim3((unsigned)grid), dim3(C::NT), LDS_BYTES, s, p);
+  hipLaunchKernelGGL((k_gemm_bf16<WGM, WGN, TM, TN, NS, EPI, GT>), dim3((unsigned)grid), dim3(C::NT), LDS_BYTES, s, p, gt);
   return ddit::hip_fail(hipGetLastError(), "gemm launch");
 }
 
@@ -763,6 +794,54 @@ int gemm_tile_choice(int epilogue, int64_t N, int n, int k, int cus, float *us_p
   if (us_per_tile)
     for (int t = 0; t < N_TILES; ++t) us_per_tile[t] = predicted_us(t, epilogue, N, n, k, cus);
   return cheapest_tile(epilogue, N, n, k, cus);
+}
+
+template <int WGM, int WGN, int TM, int TN>
+int launch_grouped_tile(const GemmParams &p, const GroupTable &gt, hipStream_t s) {
+  return launch_one<WGM, WGN, TM, TN, 4, 0, GroupTable>(p, s, gt);
+}
+
+// One launch for G problems that share u: out[g] = u W[g]^T + bias[g], every W[g] of shape [a.n, a.k].
+// Returns 1 (nothing launched) when the shape cannot be grouped: the caller then launches them one by one.
+int launch_gemm_grouped(const GemmArgs &a, int G, const void *const *W, const void *const *bias, void *const *out,
+                        hipStream_t s) {
+  if (a.N == 0 || a.n == 0 || G == 0) return 0;
+  if (G < 2 || G > MAX_GROUPS || (int64_t)G * a.n >= (int64_t)1 << 30) return 1;
+  if ((int64_t)a.n * a.k >= (int64_t)1 << 31 || a.N * a.ld_u >= (int64_t)1 << 31) return 1;
+  // cheapest tile whose columns divide a problem's out-features (a tile must lie inside one problem)
+  const int n_all = G * a.n, cus = device_cus();
+  int tile = -1;
+  float best = 0.f;
+  for (int t = 0; t < N_TILES; ++t) {
+    if (a.n % TILES[t].cols) continue;
+    const float us = predicted_us(t, 0, a.N, n_all, a.k, cus);
+    if (tile < 0 || us < best) { tile = t; best = us; }
+  }
+  if (tile < 0) return 1;
+  GroupTable gt;
+  gt.group_n = a.n;
+  for (int g = 0; g < G; ++g) {
+    gt.W[g] = reinterpret_cast<const bf16_t *>(W[g]);
+    gt.bias[g] = bias ? reinterpret_cast<const bf16_t *>(bias[g]) : nullptr;
+    gt.out[g] = reinterpret_cast<bf16_t *>(out[g]);
+  }
+  GemmParams p;
+  p.u = reinterpret_cast<const bf16_t *>(a.u); p.ld_u = a.ld_u;
+  p.W = gt.W[0]; p.bias = gt.bias[0];
+  p.N = a.N; p.n = n_all; p.k = a.k;
+  p.out = gt.out[0]; p.ld_out = a.ld_out;
+  p.resid = nullptr; p.gate_tab = nullptr; p.gate_c6 = nullptr; p.gate_c6_stride = 0;
+  p.tokens_per_sample = a.tokens_per_sample > 0 ? a.tokens_per_sample : 1;
+  p.tiles_m = 0; p.tiles_n = 0; p.group_w = 1; p.total_tiles = 0; p.rounds = 0;
+  switch (tile) {
+    case 0: return launch_grouped_tile<2, 4, 3, 3>(p, gt, s);
+    case 1: return launch_grouped_tile<2, 3, 3, 3>(p, gt, s);
+    case 2: return launch_grouped_tile<2, 4, 3, 2>(p, gt, s);
+    case 3: return launch_grouped_tile<2, 2, 3, 3>(p, gt, s);
+    case 4: return launch_grouped_tile<2, 2, 2, 3>(p, gt, s);
+    case 5: return launch_grouped_tile<2, 2, 2, 2>(p, gt, s);
+    default: return launch_grouped_tile<2, 2, 1, 2>(p, gt, s);
+  }
 }
 
 int launch_gemm(int epilogue, const GemmArgs &a, hipStream_t s) {

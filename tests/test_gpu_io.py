@@ -274,3 +274,29 @@ def test_cross_attention_cache(lib):
     with pytest.raises(lib.DditError) as e:
         lib.ddit_sample(st.shape, st.step, st.io, z0.clone(), y, valid, y_u, 2.5, 4, 0, 1, scratch, st.ws, kv, None)
     assert e.value.status == lib.DDIT_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("D,H,dh,Ly,B,n_blocks,drop_bias", [
+    (1152, 16, 72, 300, 2, 3, False),     # 2A = 2304: every output tile divides it; six layers in one launch
+    (1152, 4, 72, 77, 1, 2, True),        # one rank's share of the heads (2A = 576), ragged text length, a layer without bias
+    (144, 1, 72, 40, 2, 2, False),        # 2A = 144: no tile divides it, the layers are projected one by one
+], ids=["full-width", "head-share-no-bias", "one-by-one"])
+def test_text_kv_of_all_layers(lib, D, H, dh, Ly, B, n_blocks, drop_bias):
+    """The text k|v projections of all layers (one grouped launch where the shape allows) against the oracle."""
+    sh = syn.Shape(B, 2, 2, 2, D, H, dh, 64, Ly, n_blocks)
+    sw = syn.make_step_weights(sh, 61)
+    blocks = [syn.make_block_weights(sh, 61, i) for i in range(n_blocks)]
+    if drop_bias:
+        blocks[1]["spatial"] = {k: v for k, v in blocks[1]["spatial"].items() if k != "b_ckv"}
+    y = syn.make_activations(sh, 61)["y"]
+    shape = _shape(lib, sh)
+    d_sw, d_blocks = {k: to_dev(v) for k, v in sw.items()}, [dict_dev(b) for b in blocks]   # kept alive: the struct holds pointers
+    step = lib.step_struct(d_sw, d_blocks)
+    kv = torch.full((lib.ddit_cross_kv_bytes(shape) // 2,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lib.ddit_cross_kv_precompute(shape, step, to_dev(y), kv)
+    torch.cuda.synchronize()
+    got = dev_to_f64(kv).reshape(2 * n_blocks, B * Ly, 2 * sh.A)
+    yf = to_f64(y).reshape(B * Ly, D)
+    for layer in range(2 * n_blocks):
+        w = dict_f64(blocks[layer // 2]["temporal" if layer & 1 else "spatial"])
+        assert_parity(got[layer], ora.linear(yf, w["w_ckv"], w.get("b_ckv")), "text k|v of layer %d" % layer)
