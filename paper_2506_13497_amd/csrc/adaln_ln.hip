@@ -34,11 +34,15 @@ __global__ __launch_bounds__(256) void k_modulated_layernorm(const float *__rest
   // the first row's loads are issued before the modulation vectors are fetched
   float4 v[CHUNKS];
   auto load_row = [&](int64_t row) {
-    const float4 *xr = reinterpret_cast<const float4 *>(x + row * (int64_t)D);
+    const floatx4 *xr = reinterpret_cast<const floatx4 *>(x + row * (int64_t)D);
 #pragma unroll
     for (int j = 0; j < CHUNKS; ++j) {
       const int c = lane + 64 * j;
-      v[j] = c < nchunk ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+      v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (c < nchunk) {   // each row is read once and written once: streaming accesses
+        const floatx4 t = __builtin_nontemporal_load(xr + c);
+        v[j] = make_float4(t[0], t[1], t[2], t[3]);
+      }
     }
   };
   load_row(row0);
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(256) void k_modulated_layernorm(const float *__rest
         o[1] = (bf16_t)(dv[j].y * rstd * sc1[j].y + sh[j].y);
         o[2] = (bf16_t)(dv[j].z * rstd * sc1[j].z + sh[j].z);
         o[3] = (bf16_t)(dv[j].w * rstd * sc1[j].w + sh[j].w);
-        orow[c] = o;
+        __builtin_nontemporal_store(o, orow + c);
       }
     }
   }

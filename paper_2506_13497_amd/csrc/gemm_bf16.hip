@@ -258,7 +258,10 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TN][TM], unsigned 
           const int rl = idx / CPR, c = idx - rl * CPR;          // rl = 32 * wave-row + row
           const int64_t tok = my_row0 + (rl >> 5) * (TM * 32) + b * 32 + (rl & 31);
           const int f = my_col0 + c * 8;
-          if (tok < p.N && f < p.n) *reinterpret_cast<uintx4 *>(my_out + tok * p.ld_out + (f - my_shift)) = piece[j];
+          // streaming store: the output is not read again by this launch, and a plain store would push
+          // the operand lines that other workgroups still re-read out of the L2
+          if (tok < p.N && f < p.n)
+            __builtin_nontemporal_store(piece[j], reinterpret_cast<uintx4 *>(my_out + tok * p.ld_out + (f - my_shift)));
         }
       }
       lds_barrier();   // staged rows are read by other waves until here
@@ -295,7 +298,10 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TN][TM], unsigned 
         const int trow = (rl >> 5) * (TM * 32) + b * 32 + (rl & 31);   // row inside the tile
         const bool ok = my_row0 + trow < p.N && my_col0 + c * 4 < p.n;
         xr[slot][j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ok) xr[slot][j] = *reinterpret_cast<const float4 *>(x_tile + (trow * p.n + c * 4));
+        if (ok) {   // x is touched once per launch: streaming load and store keep it out of the operands' way
+          const floatx4 t = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(x_tile + (trow * p.n + c * 4)));
+          xr[slot][j] = make_float4(t[0], t[1], t[2], t[3]);
+        }
       }
     };
 #pragma unroll
@@ -374,11 +380,13 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[TN][TM], unsigned 
             float4 r = xr[slot][j];
             r.x += __uint_as_float(piece[j][0]); r.y += __uint_as_float(piece[j][1]);
             r.z += __uint_as_float(piece[j][2]); r.w += __uint_as_float(piece[j][3]);
-            *reinterpret_cast<float4 *>(x_tile + (trow * p.n + c * 4)) = r;
+            floatx4 rv;
+            rv[0] = r.x; rv[1] = r.y; rv[2] = r.z; rv[3] = r.w;
+            __builtin_nontemporal_store(rv, reinterpret_cast<floatx4 *>(x_tile + (trow * p.n + c * 4)));
             if (p.out) {
               bf16x4 o;
               o[0] = (bf16_t)r.x; o[1] = (bf16_t)r.y; o[2] = (bf16_t)r.z; o[3] = (bf16_t)r.w;
-              *reinterpret_cast<bf16x4 *>(p.out + (my_row0 + trow) * p.ld_out + my_col0 + c * 4) = o;
+              __builtin_nontemporal_store(o, reinterpret_cast<bf16x4 *>(p.out + (my_row0 + trow) * p.ld_out + my_col0 + c * 4));
             }
           }
         }
