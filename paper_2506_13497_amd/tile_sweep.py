@@ -91,7 +91,8 @@ def fit(tiles, data, cus):
         area = t["rows"] * t["cols"] / (128.0 * 128.0)
         x0 += [8.0 * area ** 0.75, 1.0, 2.0, 4.0]
     x0 += [1.2, 1.3, 0.3, 1.0]
-    sol = least_squares(resid, np.array(x0), loss="soft_l1", f_scale=0.1)
+    lo = [0.0] * (4 * count) + [1.0, 1.0, 0.0, 0.0]      # times are not negative, sharing a CU does not cost
+    sol = least_squares(resid, np.array(x0), loss="soft_l1", f_scale=0.1, bounds=(lo, np.inf))
     x = sol.x
     print("\nfitted constants (microseconds): rows x cols: a, e[bf16], e[GELU], e[residual]")
     for t in range(count):
