@@ -236,7 +236,9 @@ int ddit_self_attn_fwd(ddit_attn_kind kind, const ddit_shape *shape, void *q, vo
 int ddit_linear_tile_count(void);
 
 /* Geometry of one tile: out rows and columns per workgroup, wavefronts per workgroup, and how
- * many workgroups the launcher keeps resident per CU.  Any pointer may be NULL.
+ * many workgroups the launcher keeps resident per CU (a tile shape may be listed twice, once per
+ * depth of its operand pipeline: the shallower form lets one more workgroup share the CU).
+ * The list is ordered by tile area, largest first.  Any pointer may be NULL.
  * DDIT_ERR_INVALID_ARG if tile is out of range.  Host only; needs no GPU. */
 int ddit_linear_tile_info(int tile, int32_t *rows, int32_t *cols, int32_t *wavefronts,
                           int32_t *workgroups_per_cu);

@@ -704,39 +704,46 @@ int launch_one(const GemmParams &p0, hipStream_t s, const GT &gt = GT()) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Tile choice.  Seven output tiles are compiled; which is fastest depends on how the tile grid
+// Tile choice.  Nine forms of the kernel are compiled: seven output tiles, and for 192 x 192 and
+// 128 x 192 two depths of the operand ring.  With three stages two workgroups of these tiles fit a
+// CU's LDS and one's epilogue runs under the other's k loop (192 x 192 at 48600 tokens: fc1 0.62 ->
+// 0.52 ms); with four a workgroup that has the CU to itself hides more of the fetch latency (128 x
+// 192 at 3680 tokens, k = 4608: 63 against 69 microseconds).  Which form is fastest depends on how the tile grid
 // divides over the CUs far more than on the tile's own efficiency (a 192 x 384 tile runs its k
 // loop at about twice the rate per flop of a 128 x 128 one, but 60 of them leave 196 CUs idle).
 // The launcher therefore prices every tile with a small model of the kernel and takes the
 // cheapest.  With  tiles = ceil(N / rows) * ceil(n / cols)  and  q = ceil(tiles / CUs)  tiles on
 // the busiest CU,
 //     t = (a * k / 1152 + e[epilogue]) * q / gain[min(q, workgroups per CU)]
-//         * (1 + 0.40 * min(1, tiles / CUs))      [microseconds]
+//         * (1 + 0.29 * min(1, tiles / CUs)) + 0.63      [microseconds]
 // a: one workgroup's k-loop time per 1152 of k with a CU to itself; e: its epilogue and set-up;
 // gain: what sharing a CU between two or three resident workgroups returns; the load term is the
 // clock and memory slow-down of a full chip against a single busy CU.  The constants are a
 // least-squares fit (in log time) to a sweep of the model's five linears over 23 token counts
 // from 288 to 48600 with every tile forced in turn (ddit_linear_fwd_tile): over that sweep the
-// model's picks are within 0.4 % of the best tile's total time.  (Launches in the sweep follow one
-// another on a stream, so no separate launch cost shows; the fit puts it at zero.)
+// model's picks are within 0.4 % of the best tile's total time.  (The load term and the launch
+// constant trade against each other in the fit and differ between machines of one type: 0.29 / 0.63
+// and 0.40 / 0 fit equally well; the picks do not change.)
 // ---------------------------------------------------------------------------------------------
 struct TileModel {
-  int rows, cols, wavefronts, wg_per_cu;
+  int rows, cols, wavefronts, stages, wg_per_cu;   // stages: depth of the operand ring in LDS
   float a;        // k-loop microseconds per 1152 of k, alone on a CU
   float e[3];     // epilogue + set-up microseconds: bf16 / GELU / gated residual
 };
-constexpr int N_TILES = 7;
+constexpr int N_TILES = 9;
 constexpr TileModel TILES[N_TILES] = {
-    {192, 384, 8, 1, 22.30f, {4.64f, 7.66f, 18.22f}},
-    {192, 288, 6, 1, 18.88f, {4.39f, 6.84f, 15.89f}},
-    {192, 256, 8, 1, 15.63f, {3.49f, 5.33f, 12.02f}},
-    {192, 192, 4, 2, 15.05f, {2.97f, 4.43f, 11.13f}},
-    {128, 192, 4, 2, 12.45f, {1.31f, 2.24f, 6.75f}},
-    {128, 128, 4, 2, 8.74f, {1.54f, 2.05f, 5.51f}},
-    {64, 128, 4, 3, 6.36f, {0.65f, 0.79f, 2.59f}},
+    {192, 384, 8, 4, 1, 22.07f, {4.65f, 7.82f, 18.53f}},
+    {192, 288, 6, 4, 1, 18.75f, {4.28f, 6.87f, 15.69f}},
+    {192, 256, 8, 4, 1, 15.69f, {3.24f, 5.16f, 12.01f}},
+    {192, 192, 4, 3, 2, 15.24f, {2.74f, 4.34f, 11.08f}},
+    {192, 192, 4, 4, 1, 13.11f, {4.12f, 5.94f, 12.41f}},
+    {128, 192, 4, 3, 2, 12.84f, {0.67f, 1.71f, 6.39f}},
+    {128, 192, 4, 4, 1, 10.97f, {1.40f, 2.71f, 7.46f}},
+    {128, 128, 4, 4, 2, 8.91f, {1.20f, 1.75f, 5.35f}},
+    {64, 128, 4, 4, 3, 6.59f, {0.36f, 0.62f, 2.33f}},
 };
 constexpr float CU_SHARE_GAIN[3] = {1.0f, 1.21f, 1.22f};
-constexpr float FULL_CHIP_SLOWDOWN = 0.40f, LAUNCH_US = 0.0f;
+constexpr float FULL_CHIP_SLOWDOWN = 0.29f, LAUNCH_US = 0.63f;
 
 float predicted_us(int tile, int epilogue, int64_t N, int n, int k, int cus) {
   const TileModel &t = TILES[tile];
@@ -758,18 +765,12 @@ int cheapest_tile(int epilogue, int64_t N, int n, int k, int cus) {
   return best;
 }
 
-// LDS stages of a tile's operand ring.  Four, except for the two large four-wavefront tiles: with
-// three stages two of their workgroups fit a CU's LDS, and one workgroup's epilogue then runs under
-// the other's k loop (192 x 192 at 48600 tokens: fc1 0.62 -> 0.52 ms, out-projection 0.22 -> 0.19 ms).
-template <int WGM, int WGN, int TM, int TN>
-constexpr int pipeline_depth() { return WGM * WGN == 4 && TM * TN >= 6 ? 3 : 4; }
-
-template <int WGM, int WGN, int TM, int TN, int EPI>
+template <int WGM, int WGN, int TM, int TN, int NS, int EPI>
 int launch_checked(int tile, const GemmParams &p, hipStream_t s) {
-  constexpr int NS = pipeline_depth<WGM, WGN, TM, TN>();
   using C = GemmCfg<WGM, WGN, TM, TN, NS>;
   // the model's table and the compiled tile must describe the same thing
-  if (TILES[tile].rows != C::BM || TILES[tile].cols != C::BN || TILES[tile].wavefronts != C::NW) {
+  if (TILES[tile].rows != C::BM || TILES[tile].cols != C::BN || TILES[tile].wavefronts != C::NW ||
+      TILES[tile].stages != NS) {
     ddit::set_error("linear: tile table entry %d does not match its kernel", tile);
     return -2;
   }
@@ -780,13 +781,15 @@ template <int EPI>
 int launch_epi(int tile, const GemmParams &p, hipStream_t s) {
   if (tile < 0) tile = cheapest_tile(EPI, p.N, p.n, p.k, ddit::device_cus());
   switch (tile) {
-    case 0: return launch_checked<2, 4, 3, 3, EPI>(tile, p, s);
-    case 1: return launch_checked<2, 3, 3, 3, EPI>(tile, p, s);
-    case 2: return launch_checked<2, 4, 3, 2, EPI>(tile, p, s);
-    case 3: return launch_checked<2, 2, 3, 3, EPI>(tile, p, s);
-    case 4: return launch_checked<2, 2, 2, 3, EPI>(tile, p, s);
-    case 5: return launch_checked<2, 2, 2, 2, EPI>(tile, p, s);
-    case 6: return launch_checked<2, 2, 1, 2, EPI>(tile, p, s);
+    case 0: return launch_checked<2, 4, 3, 3, 4, EPI>(tile, p, s);
+    case 1: return launch_checked<2, 3, 3, 3, 4, EPI>(tile, p, s);
+    case 2: return launch_checked<2, 4, 3, 2, 4, EPI>(tile, p, s);
+    case 3: return launch_checked<2, 2, 3, 3, 3, EPI>(tile, p, s);
+    case 4: return launch_checked<2, 2, 3, 3, 4, EPI>(tile, p, s);
+    case 5: return launch_checked<2, 2, 2, 3, 3, EPI>(tile, p, s);
+    case 6: return launch_checked<2, 2, 2, 3, 4, EPI>(tile, p, s);
+    case 7: return launch_checked<2, 2, 2, 2, 4, EPI>(tile, p, s);
+    case 8: return launch_checked<2, 2, 1, 2, 4, EPI>(tile, p, s);
   }
   ddit::set_error("linear: no tile %d (there are %d)", tile, N_TILES);
   return -1;
@@ -812,9 +815,9 @@ int gemm_tile_choice(int epilogue, int64_t N, int n, int k, int cus, float *us_p
   return cheapest_tile(epilogue, N, n, k, cus);
 }
 
-template <int WGM, int WGN, int TM, int TN>
+template <int WGM, int WGN, int TM, int TN, int NS>
 int launch_grouped_tile(const GemmParams &p, const GroupTable &gt, hipStream_t s) {
-  return launch_one<WGM, WGN, TM, TN, pipeline_depth<WGM, WGN, TM, TN>(), 0, GroupTable>(p, s, gt);
+  return launch_one<WGM, WGN, TM, TN, NS, 0, GroupTable>(p, s, gt);
 }
 
 // One launch for G problems that share u: out[g] = u W[g]^T + bias[g], every W[g] of shape [a.n, a.k].
@@ -850,13 +853,15 @@ int launch_gemm_grouped(const GemmArgs &a, int G, const void *const *W, const vo
   p.tokens_per_sample = a.tokens_per_sample > 0 ? a.tokens_per_sample : 1;
   p.tiles_m = 0; p.tiles_n = 0; p.group_w = 1; p.total_tiles = 0; p.rounds = 0;
   switch (tile) {
-    case 0: return launch_grouped_tile<2, 4, 3, 3>(p, gt, s);
-    case 1: return launch_grouped_tile<2, 3, 3, 3>(p, gt, s);
-    case 2: return launch_grouped_tile<2, 4, 3, 2>(p, gt, s);
-    case 3: return launch_grouped_tile<2, 2, 3, 3>(p, gt, s);
-    case 4: return launch_grouped_tile<2, 2, 2, 3>(p, gt, s);
-    case 5: return launch_grouped_tile<2, 2, 2, 2>(p, gt, s);
-    default: return launch_grouped_tile<2, 2, 1, 2>(p, gt, s);
+    case 0: return launch_grouped_tile<2, 4, 3, 3, 4>(p, gt, s);
+    case 1: return launch_grouped_tile<2, 3, 3, 3, 4>(p, gt, s);
+    case 2: return launch_grouped_tile<2, 4, 3, 2, 4>(p, gt, s);
+    case 3: return launch_grouped_tile<2, 2, 3, 3, 3>(p, gt, s);
+    case 4: return launch_grouped_tile<2, 2, 3, 3, 4>(p, gt, s);
+    case 5: return launch_grouped_tile<2, 2, 2, 3, 3>(p, gt, s);
+    case 6: return launch_grouped_tile<2, 2, 2, 3, 4>(p, gt, s);
+    case 7: return launch_grouped_tile<2, 2, 2, 2, 4>(p, gt, s);
+    default: return launch_grouped_tile<2, 2, 1, 2, 4>(p, gt, s);
   }
 }
 
