@@ -325,25 +325,32 @@ def main():
     if not args.no_cpu:
         from oracle import stdit_oracle as ora
         f64 = lambda a: syn.bits_to_f64(a) if a.dtype == np.uint16 else a.astype(np.float64)
-        Ts = 1                # one frame of the same frame size: every stage is linear in frames
-        shs = syn.small_variant(sh, T=Ts)
-        wl = {k: v.double().cpu().numpy() for k, v in blocks[0]["spatial"].items()}
-        xs = x_in[:, :Ts].double().cpu().numpy()
+        # a third of the frames through a spatial layer and a third of the locations through a temporal
+        # layer (same token count): every stage is linear in frames resp. locations, so each scales to its layer
+        Ts = max(1, sh.T // 3)
+        Ss = max(1, sh.S // 3)
+        wl_s = {k: v.double().cpu().numpy() for k, v in blocks[0]["spatial"].items()}
+        wl_t = {k: v.double().cpu().numpy() for k, v in blocks[0]["temporal"].items()}
+        xs_s = x_in[:, :Ts].contiguous().double().cpu().numpy()
+        xs_t = x_in[:, :, :Ss].contiguous().double().cpu().numpy()
         ys = y.double().cpu().numpy()
         c6s = f64(syn.make_c6(sh, base, 0.5))
         tc = time.perf_counter()
-        ora.layer_fwd("spatial", xs, ys, np.array(valid), c6s, wl, sh.H, sh.dh)
-        dt = time.perf_counter() - tc
-        layers = 2 * sh.n_blocks
-        est_ms = dt * (sh.T / Ts) * layers * 1e3
+        ora.layer_fwd("spatial", xs_s, ys, np.array(valid), c6s, wl_s, sh.H, sh.dh)
+        dt_s = time.perf_counter() - tc
+        tc = time.perf_counter()
+        ora.layer_fwd("temporal", xs_t, ys, np.array(valid), c6s, wl_t, sh.H, sh.dh)
+        dt_t = time.perf_counter() - tc
+        est_ms = (dt_s * sh.T / Ts + dt_t * sh.S / Ss) * sh.n_blocks * 1e3
         try:
             from threadpoolctl import threadpool_info
             nthr = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             nthr = os.cpu_count()
         cpu = {"value": round(est_ms, 1), "unit": "ms", "cores": int(nthr), "kind": "oracle",
-               "sample": "one spatial layer of the fp64 numpy oracle on %d of %d frames (%d tokens), %.1f s; scaled x%.1f "
-                         "frames x%d layers to a full step" % (Ts, sh.T, shs.N, dt, sh.T / Ts, layers)}
+               "sample": "fp64 numpy oracle: one spatial layer on %d of %d frames (%.1f s) and one temporal layer on %d of "
+                         "%d locations (%.1f s), %d tokens each; scaled to whole layers x%d blocks = a full step"
+                         % (Ts, sh.T, dt_s, Ss, sh.S, dt_t, sh.B * Ts * sh.S, sh.n_blocks)}
 
     out = {
         "metric": "DiT denoise-step latency (ms) at %s-shaped latents; attention TFLOP/s in 'stages'" %

@@ -143,7 +143,7 @@ def test_linear(lib, N, n, k, epi):
     _check_linear(lib, N, n, k, epi, -1)
 
 
-N_TILES = 7
+N_TILES = 9   # forms of the kernel compiled into the library (parametrisation needs it before the library loads)
 TILE_CASES = [
     (403, 872, 1160),     # ragged in rows and columns for every tile shape, k tail
     (1, 8, 8),            # one partial tile, one partial k-step
