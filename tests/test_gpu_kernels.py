@@ -148,6 +148,8 @@ TILE_CASES = [
     (403, 872, 1160),     # ragged in rows and columns for every tile shape, k tail
     (1, 8, 8),            # one partial tile, one partial k-step
     (700, 1152, 288),     # narrow k, several row tiles
+    (26000, 864, 296),    # more tiles than resident workgroups for every form (680 of 192 x 192 on 512 slots, 2856 of
+                          # 64 x 128 on 768): the persistent loop's later rounds, fetching the next tile under the epilogue
 ]
 
 
