@@ -134,6 +134,10 @@ LIN_CASES = [
     (12900, 1152, 288),   # narrow attention width as k, ragged token tail, tiles over two samples
     (5000, 4608, 1160),   # k tail on the large tile
     (5600, 2440, 512),    # n not a multiple of 384: ragged last out-feature tile
+    # per-rank shapes of the step-time table, where the launcher picks the mid-size forms:
+    (7360, 3456, 1152),   # 360p at parallel size 2, q|k|v: 192 x 192, two workgroups per CU, several rounds
+    (24300, 1152, 1152),  # 480p at parallel size 2, out-projection: the same form with the residual epilogue
+    (3680, 1152, 4608),   # 360p at parallel size 4, fc2: 128 x 192 with the CU to itself, long k
 ]
 
 
