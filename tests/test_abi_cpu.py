@@ -178,6 +178,23 @@ def test_qk_norm_rope_validation_and_workspace(m):
     assert m.ddit_workspace_bytes(_shape(m, flags=m.DDIT_FLAG_QK_NORM)) == plain
 
 
+def test_zero_tokens_is_a_successful_no_op(m):
+    """The degenerate size: a stage called on zero token rows validates its arguments, enqueues nothing
+    and returns OK (so it needs no GPU); bad arguments are still refused first."""
+    lib = m.binding._lib
+    P = C.c_void_p
+    lin = lambda N, ld_u=64: lib.ddit_linear_fwd(0, P(0x1000), ld_u, P(0x2000), None, N, 64, 64, P(0x3000), 64,
+                                                 None, None, None, -1, 1, None)
+    assert lin(0) == 0
+    assert lin(0, ld_u=60) == -1                  # a row stride shorter than k
+    assert lin(-1) == -1
+    ln = lambda N, x=0x1000: lib.ddit_modulated_layernorm_fwd(P(x), P(0x2000), P(0x3000), 0, N, 1, 64,
+                                                              C.c_float(1e-6), P(0x4000), None)
+    assert ln(0) == 0
+    assert ln(0, x=0x1004) == -4                  # alignment is checked before the size
+    assert ln(-1) == -1
+
+
 def test_linear_tile_list_and_cost_model(m):
     """Host side of the tile choice: the list is consistent, bad indices are refused before any
     launch, and the model's pick is the cheapest of its own prices and behaves sensibly at the
