@@ -32,6 +32,10 @@
  *    are validated before anything is enqueued; on error nothing has been launched
  *    (except DDIT_ERR_HIP, raised by a failing launch).  ddit_last_error() gives a
  *    thread-local description.  Nothing throws or aborts across this boundary.
+ *  - Sizes: a ddit_shape has every dimension >= 1.  The single-stage calls that take a
+ *    token count N of their own (ddit_linear_fwd*, ddit_modulated_layernorm_fwd,
+ *    ddit_qk_norm_rope_fwd) accept N = 0: arguments are validated, nothing is enqueued,
+ *    DDIT_OK is returned.
  *  - Arithmetic: bf16 storage, fp32 accumulation; the residual stream is fp32
  *    inside ddit_stdit_block_fwd and ddit_denoise_step and is rounded to bf16 once,
  *    at the output.

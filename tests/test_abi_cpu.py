@@ -193,6 +193,10 @@ def test_zero_tokens_is_a_successful_no_op(m):
     assert ln(0) == 0
     assert ln(0, x=0x1004) == -4                  # alignment is checked before the size
     assert ln(-1) == -1
+    qk = lambda N: lib.ddit_qk_norm_rope_fwd(P(0x1000), 3456, N, 16, 72, P(0x2000), P(0x3000), C.c_float(1e-6), 1, 1,
+                                             None, None)
+    assert qk(0) == 0
+    assert qk(-1) == -1
 
 
 def test_linear_tile_list_and_cost_model(m):
