@@ -50,7 +50,7 @@
 extern "C" {
 #endif
 
-#define DDIT_ABI_VERSION 6u
+#define DDIT_ABI_VERSION 7u
 
 typedef enum {
   DDIT_OK = 0,
@@ -163,6 +163,22 @@ int ddit_attn_fwd(ddit_attn_kind kind, const ddit_shape *shape, const void *q, c
 int ddit_stdit_block_fwd(const ddit_shape *shape, const ddit_block_weights *weights, const void *x_in,
                          const void *y, const int32_t *y_valid_len_host, const float *c6, void *x_out,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ddit_stdit_block_fwd for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * block's workspace is a device array built into the library, DDIT_STATIC_SCRATCH_BYTES per GPU,
+ * held from the library's load until the process ends.  The call allocates and frees nothing.
+ * Same arguments and results as ddit_stdit_block_fwd, less the workspace.  Shapes whose
+ * ddit_workspace_bytes() exceeds DDIT_STATIC_SCRATCH_BYTES are refused with DDIT_ERR_WORKSPACE
+ * (64 MiB holds a block of the 144p latent: T=16, 9x16 tokens per frame, hidden 1152);
+ * DDIT_FLAG_TAPS is refused with DDIT_ERR_UNSUPPORTED.  Every call on one GPU uses that GPU's one
+ * array: calls that overlap in time on the same GPU (different streams or threads) race on it;
+ * calls on one stream, or ordered by the caller, are safe.  The array keeps the previous call's
+ * contents; no region of it has to start at zero. */
+#define DDIT_STATIC_SCRATCH_BYTES (64u << 20)
+int ddit_stdit_block_fwd_static(const ddit_shape *shape, const ddit_block_weights *weights, const void *x_in,
+                                const void *y, const int32_t *y_valid_len_host, const float *c6, void *x_out,
+                                void *hip_stream);
 
 /* One denoising step in token space: conditioning from timesteps_host (HOST fp32[B]),
  * then shape->n_blocks blocks with an fp32 residual stream, rounded to bf16 at x_out.

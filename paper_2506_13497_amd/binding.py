@@ -24,7 +24,7 @@ TAP_NAMES = ["xh_msa", "qkv", "o", "x_after_attn", "qc", "kvc", "oc", "x_after_c
 _TAP_DTYPE = {"x_after_attn": torch.float32, "x_after_cross": torch.float32, "x_out": torch.float32}
 
 EXPORTS = ["ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_workspace_bytes", "ddit_tap_region",
-           "ddit_attn_fwd", "ddit_stdit_block_fwd", "ddit_denoise_step", "ddit_modulated_layernorm_fwd",
+           "ddit_attn_fwd", "ddit_stdit_block_fwd", "ddit_stdit_block_fwd_static", "ddit_denoise_step", "ddit_modulated_layernorm_fwd",
            "ddit_linear_fwd", "ddit_timestep_conditioning", "ddit_io_workspace_bytes", "ddit_embed_latent",
            "ddit_embed_caption", "ddit_output_head", "ddit_eps_theta", "ddit_solver_step", "ddit_sample",
            "ddit_cross_kv_bytes", "ddit_cross_kv_precompute", "ddit_denoise_step_cached", "ddit_linear_tile_count",
@@ -115,6 +115,8 @@ def _load() -> C.CDLL:
     lib.ddit_stdit_block_fwd.argtypes = [C.POINTER(ddit_shape), C.POINTER(ddit_block_weights), C.c_void_p, C.c_void_p,
                                          C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                          C.c_void_p]
+    lib.ddit_stdit_block_fwd_static.argtypes = [C.POINTER(ddit_shape), C.POINTER(ddit_block_weights), C.c_void_p,
+                                                C.c_void_p, C.POINTER(C.c_int32), C.c_void_p, C.c_void_p, C.c_void_p]
     lib.ddit_denoise_step.argtypes = [C.POINTER(ddit_shape), C.POINTER(ddit_step_weights), C.c_void_p, C.c_void_p,
                                       C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_size_t, C.c_void_p]
@@ -251,6 +253,14 @@ def ddit_stdit_block_fwd(shape: ddit_shape, weights: ddit_block_weights, x_in, y
     _check(_lib.ddit_stdit_block_fwd(C.byref(shape), C.byref(weights), _ptr(x_in), _ptr(y), _i32(y_valid_len),
                                      _ptr(c6), _ptr(x_out), _ptr(workspace),
                                      workspace.numel() * workspace.element_size(), _stream()))
+
+
+DDIT_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def ddit_stdit_block_fwd_static(shape: ddit_shape, weights: ddit_block_weights, x_in, y, y_valid_len, c6, x_out) -> None:
+    _check(_lib.ddit_stdit_block_fwd_static(C.byref(shape), C.byref(weights), _ptr(x_in), _ptr(y), _i32(y_valid_len),
+                                            _ptr(c6), _ptr(x_out), _stream()))
 
 
 def ddit_denoise_step(shape: ddit_shape, weights: ddit_step_weights, x_in, y, y_valid_len, timesteps, temb, x_out,

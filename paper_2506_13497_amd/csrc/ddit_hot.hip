@@ -39,6 +39,35 @@ int device_cus() {
 
 namespace {
 
+#define DDIT_HIP_TRY(expr, what) do { int rc_ = hip_fail((expr), (what)); if (rc_ != DDIT_OK) return rc_; } while (0)
+
+// Scratch of the entry point that allocates nothing (ddit_stdit_block_fwd_static): the block's
+// workspace lives in this file-scope device array.  Every GPU the library runs on holds its own copy
+// at its own address until the process ends; host code never passes the array's name to a kernel, only
+// the address hipGetSymbolAddress returns for the current device (kept per device below).
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)DDIT_STATIC_SCRATCH_BYTES;
+constexpr int STATIC_SCRATCH_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+static void *g_scratch_ptr[STATIC_SCRATCH_MAX_DEVICES];   // benign race: every thread stores the same address
+
+// device address of `scratch` on the current device, looked up once per device
+int static_scratch(void **ptr_out) {
+  int dev = -1;
+  DDIT_HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
+  if (dev < 0 || dev >= STATIC_SCRATCH_MAX_DEVICES) {
+    set_error("device index %d outside the %d this library keeps scratch for", dev, STATIC_SCRATCH_MAX_DEVICES);
+    return DDIT_ERR_UNSUPPORTED;
+  }
+  void *p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    DDIT_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+    if (!p) { set_error("hipGetSymbolAddress(scratch) returned a null address"); return DDIT_ERR_HIP; }
+    __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);
+  }
+  *ptr_out = p;
+  return DDIT_OK;
+}
+
 inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -486,6 +515,27 @@ int ddit_stdit_block_fwd(const ddit_shape *shape, const ddit_block_weights *weig
   tp.layer = 1;
   DDIT_TRY(run_layer(DDIT_ATTN_TEMPORAL, d, weights->temporal, y, nullptr, y_valid_len_host, c6, shape->ln_eps, shape->flags, ws, lo, tp, s));
   return launch_cast_f32_to_bf16(x, x_out, d.N * d.D, s);
+}
+
+int ddit_stdit_block_fwd_static(const ddit_shape *shape, const ddit_block_weights *weights, const void *x_in,
+                                const void *y, const int32_t *y_valid_len_host, const float *c6, void *x_out,
+                                void *hip_stream) {
+  Dims d;
+  DDIT_TRY(check_shape(shape, &d));
+  if (shape->flags & DDIT_FLAG_TAPS) {
+    set_error("ddit_stdit_block_fwd_static keeps no taps: clear DDIT_FLAG_TAPS"); return DDIT_ERR_UNSUPPORTED;
+  }
+  Layout lo;
+  make_layout(d, shape->flags, &lo);
+  if (lo.total > STATIC_SCRATCH_BYTES) {
+    set_error("this shape needs %zu bytes of workspace; the built-in scratch of ddit_stdit_block_fwd_static holds %zu "
+              "(use ddit_stdit_block_fwd with a caller-owned workspace)", lo.total, STATIC_SCRATCH_BYTES);
+    return DDIT_ERR_WORKSPACE;
+  }
+  void *ws = nullptr;
+  DDIT_TRY(static_scratch(&ws));
+  // nothing in the block's workspace has to start at zero: every region is written before it is read
+  return ddit_stdit_block_fwd(shape, weights, x_in, y, y_valid_len_host, c6, x_out, ws, STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 int ddit_timestep_conditioning(const ddit_shape *shape, const ddit_step_weights *weights,

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol(m):
     for n in names:
         assert hasattr(lib, n), "missing export " + n
     assert sorted(m.binding.EXPORTS) == names
-    assert m.ddit_abi_version() == 6
+    assert m.ddit_abi_version() == 7
 
 
 def test_status_strings(m):
