@@ -406,7 +406,8 @@ typedef enum { DDIT_SCHED_START = 0, DDIT_SCHED_PROMOTE = 1, DDIT_SCHED_DIT_DONE
 typedef struct { int64_t time_us; int32_t kind, request, gpu_start, gpu_count; } ddit_sched_event;
 typedef struct { int64_t occupancy_gpu_us, makespan_us; } ddit_sched_totals;
 
-/* Serves requests_host[0 .. n_requests-1] (ordered by arrival) and reports what happened.
+/* Serves requests_host[0 .. n_requests-1] (ordered by arrival, at most 2^22 of them) and reports what happened.
+ * Host memory that runs out is reported as DDIT_ERR_UNSUPPORTED ("out of host memory"), never thrown.
  * Rules (the first four are the paper's, the rest are this library's readings of what it leaves open):
  *  - first come, first served; a waiting request asks for B(r) GPUs and goes down (B, B/2, .., 1)
  *    until the allocator has a block; below B it is "hungry";

@@ -4,6 +4,7 @@
 #include "../../include/ddit_hot.h"
 
 #include <stdarg.h>
+#include <algorithm>
 #include <stdio.h>
 #include <string.h>
 
@@ -102,6 +103,17 @@ int check_shape(const ddit_shape *sh, Dims *d) {
   d->B = sh->B; d->T = sh->T; d->S = (int64_t)sh->Hp * sh->Wp; d->L = d->T * d->S; d->N = d->B * d->L;
   d->D = sh->D; d->H = sh->H; d->dh = sh->dh; d->A = A; d->M = sh->M; d->Ly = sh->Ly; d->n_blocks = sh->n_blocks;
   if (d->N > (int64_t)1 << 30) { set_error("B*T*S=%lld tokens: too many", (long long)d->N); return DDIT_ERR_UNSUPPORTED; }
+  // The linears index activations and weights with 31 bits; refuse here, before anything is enqueued, every
+  // shape one of a layer's launches would refuse later (activation rows of width D, 3A, M; the text rows; the
+  // largest weights).
+  const int64_t widest = std::max<int64_t>(std::max<int64_t>(3 * A, sh->M), sh->D), lim = (int64_t)1 << 31;
+  if (d->N * widest >= lim) {
+    set_error("B*T*S * max(3*H*dh, M, D) = %lld x %lld exceeds the 31-bit index range of the linears: split the batch",
+              (long long)d->N, (long long)widest);
+    return DDIT_ERR_UNSUPPORTED;
+  }
+  if (d->B * d->Ly * d->D >= lim) { set_error("B*Ly*D=%lld exceeds the 31-bit index range of the linears", (long long)(d->B * d->Ly * d->D)); return DDIT_ERR_UNSUPPORTED; }
+  if ((int64_t)sh->M * sh->D >= lim) { set_error("M*D=%lld exceeds the 31-bit weight index range", (long long)sh->M * sh->D); return DDIT_ERR_UNSUPPORTED; }
   return DDIT_OK;
 }
 

@@ -10,6 +10,7 @@
 #include "../../include/ddit_hot.h"
 
 #include <algorithm>
+#include <exception>
 #include <new>
 #include <set>
 #include <utility>
@@ -18,6 +19,8 @@
 using ddit::set_error;
 
 namespace {
+
+constexpr int MAX_REQUESTS = 1 << 22;   // bounds the simulation's host memory (a few hundred bytes per request)
 
 inline bool pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
 inline int log2i(int64_t v) { int k = 0; while ((int64_t)1 << (k + 1) <= v) ++k; return k; }
@@ -125,16 +128,15 @@ int ddit_optimal_dop(const int64_t *step_us_row_host, int32_t n_dop, int64_t z_m
   return DDIT_OK;
 }
 
-int ddit_buddy_create(int32_t n_gpus, void **pool_out) {
+static int ddit_buddy_create_impl(int32_t n_gpus, void **pool_out) {
   if (!pool_out) { set_error("pool_out is NULL"); return DDIT_ERR_INVALID_ARG; }
   if (!pow2(n_gpus) || n_gpus > 4096) { set_error("n_gpus=%d must be a power of two, at most 4096", n_gpus); return DDIT_ERR_INVALID_ARG; }
-  BuddyPool *b = new (std::nothrow) BuddyPool(n_gpus);
-  if (!b) { set_error("out of host memory"); return DDIT_ERR_INVALID_ARG; }
+  BuddyPool *b = new BuddyPool(n_gpus);   // may throw: the caller below is guarded
   *pool_out = b;
   return DDIT_OK;
 }
 
-int ddit_buddy_alloc(void *pool, int32_t size, int32_t *start_out) {
+static int ddit_buddy_alloc_impl(void *pool, int32_t size, int32_t *start_out) {
   BuddyPool *b = reinterpret_cast<BuddyPool *>(pool);
   if (!b || !start_out) { set_error("pool and start_out must not be NULL"); return DDIT_ERR_INVALID_ARG; }
   if (!pow2(size) || size > b->n) { set_error("size=%d must be a power of two, at most %d", size, b->n); return DDIT_ERR_INVALID_ARG; }
@@ -142,7 +144,7 @@ int ddit_buddy_alloc(void *pool, int32_t size, int32_t *start_out) {
   return DDIT_OK;
 }
 
-int ddit_buddy_release(void *pool, int32_t start, int32_t size) {
+static int ddit_buddy_release_impl(void *pool, int32_t start, int32_t size) {
   BuddyPool *b = reinterpret_cast<BuddyPool *>(pool);
   if (!b) { set_error("pool is NULL"); return DDIT_ERR_INVALID_ARG; }
   if (!pow2(size) || size > b->n || start < 0 || start % size || start + size > b->n) {
@@ -154,7 +156,7 @@ int ddit_buddy_release(void *pool, int32_t start, int32_t size) {
   return DDIT_OK;
 }
 
-int ddit_buddy_free_gpus(void *pool, int32_t *free_out) {
+static int ddit_buddy_free_gpus_impl(void *pool, int32_t *free_out) {
   BuddyPool *b = reinterpret_cast<BuddyPool *>(pool);
   if (!b || !free_out) { set_error("pool and free_out must not be NULL"); return DDIT_ERR_INVALID_ARG; }
   *free_out = b->free_gpus();
@@ -166,11 +168,12 @@ int ddit_buddy_destroy(void *pool) {
   return DDIT_OK;
 }
 
-int ddit_sched_simulate(const ddit_sched_config *config, const ddit_sched_request *requests_host, int32_t n_requests,
+static int ddit_sched_simulate_impl(const ddit_sched_config *config, const ddit_sched_request *requests_host, int32_t n_requests,
                         ddit_sched_record *records_out, ddit_sched_event *events_out_or_null, int64_t max_events,
                         int64_t *n_events_out, ddit_sched_totals *totals_out) {
   int rc = check_config(config);
   if (rc != DDIT_OK) return rc;
+  if (n_requests > MAX_REQUESTS) { set_error("n_requests=%d: at most %d requests per call", n_requests, MAX_REQUESTS); return DDIT_ERR_UNSUPPORTED; }
   if (n_requests < 0 || (n_requests > 0 && (!requests_host || !records_out))) { set_error("requests / records missing for n_requests=%d", n_requests); return DDIT_ERR_INVALID_ARG; }
   if (max_events < 0 || (max_events > 0 && !events_out_or_null)) { set_error("max_events=%lld without an event array", (long long)max_events); return DDIT_ERR_INVALID_ARG; }
   const ddit_sched_config &c = *config;
@@ -320,6 +323,33 @@ int ddit_sched_simulate(const ddit_sched_config *config, const ddit_sched_reques
     totals_out->makespan_us = now;
   }
   return DDIT_OK;
+}
+
+// Nothing may throw across the C boundary: the containers above allocate host memory, so every call that
+// touches them runs guarded and turns an exception into a status and an error text.
+#define DDIT_GUARDED(call)                                                                       \
+  try {                                                                                          \
+    return call;                                                                                 \
+  } catch (const std::bad_alloc &) {                                                             \
+    set_error("out of host memory");                                                             \
+    return DDIT_ERR_UNSUPPORTED;                                                                 \
+  } catch (const std::exception &e) {                                                            \
+    set_error("host exception: %s", e.what());                                                   \
+    return DDIT_ERR_INVALID_ARG;                                                                 \
+  } catch (...) {                                                                                \
+    set_error("unknown host exception");                                                         \
+    return DDIT_ERR_INVALID_ARG;                                                                 \
+  }
+
+int ddit_buddy_create(int32_t n_gpus, void **pool_out) { DDIT_GUARDED(ddit_buddy_create_impl(n_gpus, pool_out)) }
+int ddit_buddy_alloc(void *pool, int32_t size, int32_t *start_out) { DDIT_GUARDED(ddit_buddy_alloc_impl(pool, size, start_out)) }
+int ddit_buddy_release(void *pool, int32_t start, int32_t size) { DDIT_GUARDED(ddit_buddy_release_impl(pool, start, size)) }
+int ddit_buddy_free_gpus(void *pool, int32_t *free_out) { DDIT_GUARDED(ddit_buddy_free_gpus_impl(pool, free_out)) }
+int ddit_sched_simulate(const ddit_sched_config *config, const ddit_sched_request *requests_host, int32_t n_requests,
+                        ddit_sched_record *records_out, ddit_sched_event *events_out_or_null, int64_t max_events,
+                        int64_t *n_events_out, ddit_sched_totals *totals_out) {
+  DDIT_GUARDED(ddit_sched_simulate_impl(config, requests_host, n_requests, records_out, events_out_or_null, max_events,
+                                        n_events_out, totals_out))
 }
 
 }  // extern "C"

@@ -11,7 +11,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 LIB = os.path.join(ROOT, "paper_2506_13497_amd", "libddit_hot.so")
 HEADER = os.path.join(ROOT, "include", "ddit_hot.h")
 
-pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libddit_hot.so not built (run __graft_entry__.build())")
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _library_is_built():
+    # a missing library is a failure of the build, not a reason to skip: nothing below can be trusted without it
+    assert os.path.exists(LIB), "libddit_hot.so is not built: run __graft_entry__.build() (or python -m paper_2506_13497_amd.build)"
 
 
 @pytest.fixture(scope="module")
@@ -65,6 +70,11 @@ def test_workspace_bytes_and_layout_monotone(m):
 @pytest.mark.parametrize("kw,code", [
     (dict(dh=80), -2), (dict(H=8, dh=64), -2), (dict(D=250), -2), (dict(B=0), -1), (dict(Ly=0), -1),
     (dict(B=65), -2), (dict(D=8192, H=4), -2),
+    # 5 samples of the 720p shape: 540000 tokens x 4608 passes 2^31, which the linears' 31-bit indices cannot hold;
+    # refused here, before any layer's kernels are enqueued
+    (dict(B=5, T=30, Hp=45, Wp=80, D=1152, H=16, dh=72, M=4608, Ly=300, n_blocks=28), -2),
+    (dict(B=64, T=30, Hp=45, Wp=80, D=1152, H=4, dh=72, M=4608, Ly=300), -2),
+    (dict(M=1 << 24), -2),
 ])
 def test_bad_shapes_are_rejected(m, kw, code):
     with pytest.raises(m.binding.DditError) as e:

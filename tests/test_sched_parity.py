@@ -149,3 +149,14 @@ def test_argument_validation(m):
         m.ddit_optimal_dop([5, 4], 1, 0)
     with pytest.raises(m.DditError):
         m.ddit_optimal_dop([5, 0])
+
+
+def test_request_count_is_bounded(m):
+    """More requests than the documented bound are refused up front (status, not an exception or an
+    unbounded host allocation)."""
+    lib = m.binding._lib
+    step = (C.c_int64 * 1)(5)
+    opt = (C.c_int32 * 1)(1)
+    cfg = m.binding.ddit_sched_config(C.sizeof(m.binding.ddit_sched_config), 1, 1, 1, 1, 1, step, opt, None)
+    assert lib.ddit_sched_simulate(C.byref(cfg), None, (1 << 22) + 1, None, None, 0, None, None) == m.DDIT_ERR_UNSUPPORTED
+    assert "at most" in m.ddit_last_error()
