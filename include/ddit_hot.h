@@ -283,6 +283,22 @@ int ddit_timestep_conditioning(const ddit_shape *shape, const ddit_step_weights 
                                const float *timesteps_host, const float *temb_or_null, float *c6_out,
                                float *scratch, void *hip_stream);
 
+/* ---- measurement probes: the denominators the kernels are held against, reproducible on any box ----
+ * None is on the hot path; the benchmark times them beside the step.
+ * ddit_probe_mfma_bf16: a register-resident loop of the bf16 matrix-core instruction the linears and the
+ *   attention use, 2 workgroups of 4 wavefronts per compute unit, 12 independent accumulators each, `iters`
+ *   rounds; `operands` = 64 KiB of bf16 the fragments are taken from (the sustained clock depends on the data:
+ *   constant data runs faster than random data), `sink` = device fp32, 512 floats per compute unit;
+ *   *flop_out (HOST, optional) receives the floating-point operations of the launch.
+ * ddit_probe_stream_copy: out[0..bytes) = in[0..bytes) with streaming 16-byte loads and stores.
+ * ddit_probe_residual_stream: the memory traffic of an out-projection with gated residual update and none of
+ *   its matrix work: per token row reads A bf16 of o and D fp32 of x, writes D fp32 of x and D bf16 of xh_out
+ *   (x += gate * f(o) with a cheap f; the result has no meaning).  gate: device fp32 [D]. */
+int ddit_probe_mfma_bf16(const void *operands, float *sink, int32_t iters, double *flop_out, void *hip_stream);
+int ddit_probe_stream_copy(const void *in, void *out, int64_t bytes, void *hip_stream);
+int ddit_probe_residual_stream(float *x, void *xh_out, const void *o, const float *gate, int64_t N, int32_t D,
+                               int32_t A, void *hip_stream);
+
 /* ---- latent in, latent out, and the sampling loop of eq. 1 -------------------------------
  *
  * Section 2.1 states the reverse process: from Gaussian noise x_T, each step calls the model on

@@ -30,7 +30,7 @@ EXPORTS = ["ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_wo
            "ddit_cross_kv_bytes", "ddit_cross_kv_precompute", "ddit_denoise_step_cached", "ddit_linear_tile_count",
            "ddit_linear_tile_info", "ddit_linear_tile_choice", "ddit_linear_fwd_tile", "ddit_qk_norm_rope_fwd", "ddit_self_attn_fwd", "ddit_optimal_dop",
            "ddit_buddy_create", "ddit_buddy_alloc", "ddit_buddy_release", "ddit_buddy_free_gpus", "ddit_buddy_destroy",
-           "ddit_sched_simulate"]
+           "ddit_sched_simulate", "ddit_probe_mfma_bf16", "ddit_probe_stream_copy", "ddit_probe_residual_stream"]
 
 
 class ddit_shape(C.Structure):
@@ -159,6 +159,9 @@ def _load() -> C.CDLL:
     lib.ddit_solver_step.argtypes = [VP, VP, VP, C.c_float, FP, FP, C.c_int32, C.c_int64, VP]
     lib.ddit_sample.argtypes = [SP, WP, IP, VP, VP, C.POINTER(C.c_int32), VP, VP, VP, C.c_float, C.c_int32, C.c_int32,
                                 C.c_int32, VP, VP, C.c_size_t, VP]
+    lib.ddit_probe_mfma_bf16.argtypes = [VP, VP, C.c_int32, C.POINTER(C.c_double), VP]
+    lib.ddit_probe_stream_copy.argtypes = [VP, VP, C.c_int64, VP]
+    lib.ddit_probe_residual_stream.argtypes = [VP, VP, VP, VP, C.c_int64, C.c_int32, C.c_int32, VP]
     for n in EXPORTS:
         if n not in ("ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_linear_tile_count"):
             getattr(lib, n).restype = C.c_int
@@ -462,6 +465,21 @@ def ddit_sample(shape: ddit_shape, weights: ddit_step_weights, io: ddit_io_weigh
     _check(_lib.ddit_sample(C.byref(shape), C.byref(weights), C.byref(io), _ptr(z), _ptr(y), _i32(y_valid_len),
                             _ptr(y_uncond), _ptr(cross_kv), _ptr(cross_kv_uncond), guidance, n_steps, first_step,
                             last_step, _ptr(eps_scratch), _ptr(workspace), _nbytes(workspace), _stream()))
+
+
+def ddit_probe_mfma_bf16(operands, sink, iters: int) -> float:
+    """-> floating-point operations of the launch."""
+    fl = C.c_double(0.0)
+    _check(_lib.ddit_probe_mfma_bf16(_ptr(operands), _ptr(sink), iters, C.byref(fl), _stream()))
+    return fl.value
+
+
+def ddit_probe_stream_copy(src, dst, nbytes: int) -> None:
+    _check(_lib.ddit_probe_stream_copy(_ptr(src), _ptr(dst), nbytes, _stream()))
+
+
+def ddit_probe_residual_stream(x, xh_out, o, gate, N: int, D: int, A: int) -> None:
+    _check(_lib.ddit_probe_residual_stream(_ptr(x), _ptr(xh_out), _ptr(o), _ptr(gate), N, D, A, _stream()))
 
 
 # ----------------------------------------------------------------------------- helpers (no arithmetic)

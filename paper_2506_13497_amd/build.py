@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libddit_hot.so")
 SOURCES = ["ddit_hot.hip", "adaln_ln.hip", "gemm_bf16.hip", "flash_attn.hip", "temporal_attn.hip", "cond.hip",
-           "latent_io.hip", "qk_norm_rope.hip", "step_scheduler.hip"]
+           "latent_io.hip", "qk_norm_rope.hip", "step_scheduler.hip", "probes.hip"]
 # packed-fp32 VALU forms are switched off for all device code of this library
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
