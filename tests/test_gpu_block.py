@@ -299,13 +299,20 @@ def _stagewise_sampled(lib, cfg_name, n_rows=96, seed=0):
     c6 = syn.make_c6(sh, base, std=0.5)
     valid = syn.make_valid_len(sh, base, cfg["valid"])
     shape, ws, x_out = _run_block(lib, sh, wb, act, c6, list(valid), flags=lib.DDIT_FLAG_TAPS)
-    N, D, A, M, S, T, L, H, dh = sh.N, sh.D, sh.A, sh.M, sh.S, sh.T, sh.L, sh.H, sh.dh
     rng = np.random.default_rng(seed)
-    rows = np.unique(np.concatenate([rng.integers(0, N, n_rows), [0, N - 1]]))
+    rows = np.unique(np.concatenate([rng.integers(0, sh.N, n_rows), [0, sh.N - 1]]))
+    _check_tapped_block(lib, sh, shape, ws, x_out, wb, c6.astype(np.float64), valid, to_f64(act["y"]), rows,
+                        to_f64(act["x"]).reshape(sh.N, sh.D)[rows])
+
+
+def _check_tapped_block(lib, sh, shape, ws, x_out, wb, c6d, valid, y64, rows, x_first):
+    """Every stage of the block whose taps `ws` holds, against the oracle on the sampled `rows`, each stage fed
+    the GPU's own input to it.  x_first: the stream entering the spatial layer at those rows, or None when the
+    taps do not hold it (a step keeps the taps of its last block only): the two stages that need it (a1 and the
+    absolute value of a4 in the spatial layer) are then checked in the temporal layer alone."""
+    N, D, A, M, S, T, L, H, dh = sh.N, sh.D, sh.A, sh.M, sh.S, sh.T, sh.L, sh.H, sh.dh
     rows_t = torch.from_numpy(rows).cuda()
-    c6d = c6.astype(np.float64)
-    y64 = to_f64(act["y"])
-    x_prev = to_f64(act["x"]).reshape(N, D)[rows]      # stream entering the layer, sampled rows
+    x_prev = x_first
     for layer, kind in enumerate(("spatial", "temporal")):
         w = dict_f64(wb[kind])
         tap = lambda name, cols: _tap(lib, shape, ws, layer, name, cols)
@@ -314,7 +321,8 @@ def _stagewise_sampled(lib, cfg_name, n_rows=96, seed=0):
         mods = [ora.split_modulation(w["ada_table"], c6d[b], D) for b in range(sh.B)]
         mod = lambda nm: np.stack([mods[b][nm] for b in bidx])
         # a1: modulated LayerNorm
-        assert_parity(take("xh_msa", D), ora.modulate(ora.layer_norm(x_prev), mod("shift_msa"), mod("scale_msa")), kind + " a1")
+        if x_prev is not None:
+            assert_parity(take("xh_msa", D), ora.modulate(ora.layer_norm(x_prev), mod("shift_msa"), mod("scale_msa")), kind + " a1")
         # a2: qkv projection of the GPU's own xh
         assert_parity(take("qkv", 3 * A), ora.linear(take("xh_msa", D), w["w_qkv"], w["b_qkv"]), kind + " a2")
         # a3: attention on the GPU's own q,k,v for the sequences the sampled rows belong to (2 heads each)
@@ -330,10 +338,11 @@ def _stagewise_sampled(lib, cfg_name, n_rows=96, seed=0):
                 got = dev_to_f64(o_t[torch.from_numpy(seq).cuda()][:, h * dh:(h + 1) * dh])
                 assert_parity(got, want, "%s a3 row %d head %d" % (kind, r, h))
         # a4: out-projection + gated residual
-        x_attn = x_prev + mod("gate_msa") * ora.linear(take("o", A), w["w_o"], w["b_o"])
-        assert_parity(take("x_after_attn", D), x_attn, kind + " a4")
-        got_branch = take("x_after_attn", D) - x_prev
-        assert rel_fro(got_branch, x_attn - x_prev) < 1e-2, kind + " a4 branch"
+        if x_prev is not None:
+            x_attn = x_prev + mod("gate_msa") * ora.linear(take("o", A), w["w_o"], w["b_o"])
+            assert_parity(take("x_after_attn", D), x_attn, kind + " a4")
+            got_branch = take("x_after_attn", D) - x_prev
+            assert rel_fro(got_branch, x_attn - x_prev) < 1e-2, kind + " a4 branch"
         # a5: cross projections (q from bf16 of the GPU's stream; k|v from y, in full)
         xa_bf = dev_to_f64(tap("x_after_attn", D)[rows_t].to(torch.bfloat16))
         assert_parity(take("qc", A), ora.linear(xa_bf, w["w_cq"], w["b_cq"]), kind + " a5 q")
@@ -364,6 +373,79 @@ def _stagewise_sampled(lib, cfg_name, n_rows=96, seed=0):
         x_prev = take("x_out", D)
     # a11: the bf16 output is the rounding of the fp32 stream
     assert torch.equal(x_out.reshape(N, D), _tap(lib, shape, ws, 1, "x_out", D).to(torch.bfloat16))
+
+
+def _step_last_block_stagewise(lib, cfg_name, n_rows=64):
+    """ddit_denoise_step at the full shape and depth the benchmark times (28 blocks, per-block weights, the
+    library's own timestep conditioning), taps on: they hold the last block, whose stages are checked against the
+    oracle stage by stage on sampled rows (teacher forcing), a11 bit for bit; and the same step without taps
+    (the call the benchmark makes) must give the same output bit for bit.  Block 27's weights and the step's
+    come from the seeded numpy generator (the oracle needs them); blocks 0..26 only feed block 27 a realistic
+    stream and are drawn on the device from a seeded generator of the same distribution."""
+    cfg = syn.CONFIGS[cfg_name]; sh = cfg["shape"]; base = cfg["base"]
+    last = sh.n_blocks - 1
+    sw = syn.make_step_weights(sh, base)
+    wb_last = syn.make_block_weights(sh, base, last)
+    act = syn.make_activations(sh, base)
+    valid = syn.make_valid_len(sh, base, cfg["valid"])
+    t = syn.make_timesteps(sh, base, cfg["t"])
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4242 + base)
+    dblocks = []
+    for i in range(last):
+        dblocks.append({kind: {n: (torch.randn(s_, generator=gen, device="cuda") * 0.02).to(torch.bfloat16).to(
+            torch.float32 if n == "ada_table" else torch.bfloat16) for n, s_ in syn.layer_shapes(sh).items()}
+            for kind in ("spatial", "temporal")})
+    dblocks.append(dict_dev(wb_last))
+    dsw = {k: to_dev(v) for k, v in sw.items()}
+    st = lib.step_struct(dsw, dblocks)
+    x_in, y = to_dev(act["x"]), to_dev(act["y"])
+    outs = []
+    for flags in (lib.DDIT_FLAG_TAPS, 0):
+        shape = _shape(lib, sh, flags)
+        ws = lib.alloc_workspace(shape)
+        x_out = torch.full((sh.B, sh.T, sh.S, sh.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        lib.ddit_denoise_step(shape, st, x_in, y, list(valid), list(t), None, x_out, ws)
+        torch.cuda.synchronize()
+        outs.append(x_out)
+        if flags:
+            sw64 = dict_f64(sw)
+            c6d = ora.conditioning(ora.timestep_embedding(t.astype(np.float64), sw64), sw64)
+            rng = np.random.default_rng(7)
+            rows = np.unique(np.concatenate([rng.integers(0, sh.N, n_rows), [0, sh.N - 1]]))
+            _check_tapped_block(lib, sh, shape, ws, x_out, wb_last, c6d, valid, to_f64(act["y"]), rows, None)
+        del ws
+    assert torch.isfinite(outs[1].float()).all()
+    assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16)), "the step without taps differs from the step with taps"
+
+
+def test_step_480p_28_blocks_last_block_stagewise(lib):
+    _step_last_block_stagewise(lib, "C4")
+
+
+def test_step_720p_share_28_blocks_last_block_stagewise(lib):
+    _step_last_block_stagewise(lib, "C5")
+
+
+def test_step_240p_batch2_four_blocks_end_to_end(lib):
+    """The 240p configuration (batch 2, per-sample timesteps, full width) end to end against the fp64 oracle, with a
+    different valid text length per sample.  Depth 4 blocks = 8 layers instead of 28: the oracle needs about 40 s of
+    CPU per block at this shape (its attention loops over 13000 sequences in Python), 28 blocks would take a
+    quarter of an hour; the full-depth end-to-end comparison is the 144p test above."""
+    cfg = syn.CONFIGS["C3"]; base = cfg["base"]
+    sh = syn.small_variant(cfg["shape"], n_blocks=4)
+    sw = syn.make_step_weights(sh, base)
+    blocks = [syn.make_block_weights(sh, base, i) for i in range(sh.n_blocks)]
+    act = syn.make_activations(sh, base)
+    t = syn.make_timesteps(sh, base, cfg["t"])
+    assert t[0] != t[1]
+    valid = [77, 300]
+    _, _, x_out = _run_step(lib, sh, sw, blocks, act, valid, t=t)
+    ref = ora.denoise_step(to_f64(act["x"]), to_f64(act["y"]), valid, t.astype(np.float64), dict_f64(sw),
+                           [dict_f64(b) for b in blocks], sh.H, sh.dh)
+    assert_parity(dev_to_f64(x_out), ref, "240p batch-2 step, 4 blocks")
+    # the two samples really took different conditioning and masks: swapping them must change the result
+    assert rel_fro(dev_to_f64(x_out[0]), dev_to_f64(x_out[1])) > 0.1
 
 
 def test_full_size_480p_block_stagewise(lib):
