@@ -123,6 +123,51 @@ def dop_table(m, syn, torch, steps):
     return rows
 
 
+# the model's linears (hidden 1152, MLP 4608): name, epilogue, out-features, in-features
+SWEEP_LINEARS = [("qkv", 0, 3456, 1152), ("attn_out", 2, 1152, 1152), ("fc1", 1, 4608, 1152), ("fc2", 2, 1152, 4608),
+                 ("cross_q", 0, 1152, 1152), ("cross_kv", 0, 2304, 1152)]
+SWEEP_TOKENS = [288, 576, 920, 1215, 1840, 2304, 2880, 3240, 3680, 4320, 4860, 5760, 6480, 7360, 8640, 9720, 11520, 12960,
+                14400, 19440, 24300, 36000, 48600]
+
+
+def tile_sweep(m, torch, tokens):
+    """Every compiled output tile of the linear forced in turn (ddit_linear_fwd_tile) on the model's linears over a
+    range of token counts, beside the launcher's own pick: the table the launcher's cost model was fitted to."""
+    count = m.ddit_linear_tile_count()
+    tiles = [m.ddit_linear_tile_info(t) for t in range(count)]
+    print("tiles: " + "  ".join("%d=%dx%d" % (i, t["rows"], t["cols"]) for i, t in enumerate(tiles)))
+    print("%-9s %6s %5s %8s | " % ("linear", "N", "pick", "pick_us") + " ".join("%7s" % ("t%d_us" % i) for i in range(count))
+          + " | pick/best")
+    torch.manual_seed(0)
+    tab, c6 = torch.randn(6, 1152, device="cuda"), torch.randn(1, 6 * 1152, device="cuda")
+    ratios = []
+    for N in tokens:
+        for name, epi, n, k in SWEEP_LINEARS:
+            u, W = (torch.randn(N, k, device="cuda") * 0.5).bfloat16(), (torch.randn(n, k, device="cuda") * 0.03).bfloat16()
+            bias, out = torch.randn(n, device="cuda").bfloat16(), torch.empty(N, n, device="cuda", dtype=torch.bfloat16)
+            resid = torch.zeros(N, n, device="cuda") if epi == 2 else None
+
+            def timed(tile):
+                call = lambda: m.ddit_linear_fwd_tile(tile, epi, u, k, W, bias, N, n, k, None if epi == 2 else out, n, resid=resid,
+                                                      ada_table=tab if epi == 2 else None, c6=c6 if epi == 2 else None,
+                                                      gate_row=2 if epi == 2 else -1, tokens_per_sample=N)
+                for _ in range(3):
+                    call()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(20):
+                    call()
+                e1.record()
+                e1.synchronize()
+                return e0.elapsed_time(e1) / 20 * 1000.0
+            us = [timed(t) for t in range(count)]
+            pick, pick_us = m.ddit_linear_tile_choice(epi, N, n, k)[0], timed(-1)
+            ratios.append(pick_us / min(us))
+            print("%-9s %6d %5d %8.1f | " % (name, N, pick, pick_us) + " ".join("%7.1f" % x for x in us)
+                  + " | %.2f" % ratios[-1], flush=True)
+    print("rows %d; pick / best: mean %.3f, worst %.2f" % (len(ratios), sum(ratios) / len(ratios), max(ratios)))
+
+
 class Workload:
     """One configuration resident on the device: weights, inputs, workspace, the step call."""
 
@@ -359,6 +404,8 @@ def main():
     ap.add_argument("--no-stages", action="store_true", help="skip the per-kernel timings")
     ap.add_argument("--only-stage", default=None,
                     help="time only this entry of 'stages' (for counter runs of one kernel), e.g. spatial_attention")
+    ap.add_argument("--tile-sweep", action="store_true",
+                    help="instead of the benchmark line: every compiled tile of the linear forced in turn, beside the launcher's pick")
     ap.add_argument("--dop-table", action="store_true",
                     help="instead of the benchmark line: per-rank step time by resolution and degree of parallelism")
     args = ap.parse_args()
@@ -375,6 +422,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.tile_sweep:
+        tile_sweep(m, torch, SWEEP_TOKENS)
+        return
     if args.dop_table:
         rows = dop_table(m, syn, torch, max(args.steps // 3, 2))
         print(json.dumps({"metric": "DiT step time (ms) of one rank by resolution and degree of parallelism", "unit": "ms",

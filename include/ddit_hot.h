@@ -23,7 +23,10 @@
  *    c6 and lse are fp32.  Every device pointer must be 16-byte aligned and every
  *    leading dimension a multiple of 8 elements.
  *  - Ownership: the caller owns every buffer including the workspace; the library
- *    allocates and frees no device memory and keeps no state between calls.
+ *    allocates and frees no device memory.  Between calls it keeps no data of a call; what it does keep
+ *    per process is set once and never changes results: the compute-unit count of the device, a
+ *    "dynamic LDS size attribute set" flag per kernel, and the address of the built-in scratch of
+ *    ddit_stdit_block_fwd_static per device.
  *    Buffers must stay alive until `hip_stream` has run past the call.
  *  - Asynchrony: all work is enqueued on `hip_stream` (a hipStream_t, NULL = the
  *    default stream); no call synchronises with the host.  *_host arrays are read
@@ -157,7 +160,9 @@ int ddit_attn_fwd(ddit_attn_kind kind, const ddit_shape *shape, const void *q, c
                   int64_t ld_q, int64_t ld_kv, const int32_t *kv_valid_len_host, void *o, int64_t ld_o,
                   float *lse_or_null, void *workspace, size_t workspace_bytes, void *hip_stream);
 
-/* One block (spatial layer then temporal layer) on x_in bf16 [B,T,S,D] with text y bf16
+/* One block of the model of section 2.2 (a "spatial" Transformer layer, which mixes the tokens of one temporal
+ * index, followed by a "temporal" one, which mixes the tokens of one spatial location; each with its
+ * "cross-attention" to the conditioning text): spatial layer then temporal layer on x_in bf16 [B,T,S,D] with text y bf16
  * [B,Ly,D], valid lengths (HOST int32[B] or NULL = Ly) and conditioning c6 (device fp32
  * [B,6D]).  x_out bf16 [B,T,S,D] may alias x_in.  shape->n_blocks is ignored. */
 int ddit_stdit_block_fwd(const ddit_shape *shape, const ddit_block_weights *weights, const void *x_in,
@@ -180,7 +185,8 @@ int ddit_stdit_block_fwd_static(const ddit_shape *shape, const ddit_block_weight
                                 const void *y, const int32_t *y_valid_len_host, const float *c6, void *x_out,
                                 void *hip_stream);
 
-/* One denoising step in token space: conditioning from timesteps_host (HOST fp32[B]),
+/* One evaluation of eps_theta(x_t, t, c) of eq. 1 in token space (x_t = x_in, t = timesteps_host, c = y; the
+ * model of section 2.2 and Table 1): conditioning from timesteps_host (HOST fp32[B]),
  * then shape->n_blocks blocks with an fp32 residual stream, rounded to bf16 at x_out.
  * If temb_or_null (device fp32 [B,D]) is given it replaces the timestep embedder's
  * output (timesteps_host may then be NULL). */

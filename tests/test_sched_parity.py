@@ -14,7 +14,11 @@ from test_oracle_pins_sched import check_invariants, random_case
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 LIB = os.path.join(ROOT, "paper_2506_13497_amd", "libddit_hot.so")
-pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libddit_hot.so not built (run __graft_entry__.build())")
+
+@pytest.fixture(scope="module", autouse=True)
+def _library_is_built():
+    assert os.path.exists(LIB), "libddit_hot.so is not built: run __graft_entry__.build()"
+
 
 
 @pytest.fixture(scope="module")
