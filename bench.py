@@ -378,7 +378,10 @@ def probes(m, torch, sh):
     dst = torch.empty_like(src)
     ms = timed(lambda: m.ddit_probe_stream_copy(src, dst, nbytes))
     out["stream_copy_GBps"] = round(2.0 * nbytes / (ms * 1e-3) / 1e9, 1)
-    del src, dst
+    sink_r = torch.empty(4096 * cus, device="cuda")
+    ms = timed(lambda: m.ddit_probe_stream_read(src, nbytes, sink_r))
+    out["stream_read_GBps"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+    del src, dst, sink_r
     N, D, A = sh.N, sh.D, sh.A
     x = torch.randn(N, D, device="cuda")
     xh = torch.empty(N, D, dtype=torch.bfloat16, device="cuda")

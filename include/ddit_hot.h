@@ -297,11 +297,13 @@ int ddit_timestep_conditioning(const ddit_shape *shape, const ddit_step_weights 
  *   constant data runs faster than random data), `sink` = device fp32, 512 floats per compute unit;
  *   *flop_out (HOST, optional) receives the floating-point operations of the launch.
  * ddit_probe_stream_copy: out[0..bytes) = in[0..bytes) with streaming 16-byte loads and stores.
+ * ddit_probe_stream_read: reads in[0..bytes) with streaming 16-byte loads; sink: device fp32, 4096 floats per compute unit.
  * ddit_probe_residual_stream: the memory traffic of an out-projection with gated residual update and none of
  *   its matrix work: per token row reads A bf16 of o and D fp32 of x, writes D fp32 of x and D bf16 of xh_out
  *   (x += gate * f(o) with a cheap f; the result has no meaning).  gate: device fp32 [D]. */
 int ddit_probe_mfma_bf16(const void *operands, float *sink, int32_t iters, double *flop_out, void *hip_stream);
 int ddit_probe_stream_copy(const void *in, void *out, int64_t bytes, void *hip_stream);
+int ddit_probe_stream_read(const void *in, int64_t bytes, float *sink, void *hip_stream);
 int ddit_probe_residual_stream(float *x, void *xh_out, const void *o, const float *gate, int64_t N, int32_t D,
                                int32_t A, void *hip_stream);
 

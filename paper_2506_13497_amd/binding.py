@@ -30,7 +30,7 @@ EXPORTS = ["ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_wo
            "ddit_cross_kv_bytes", "ddit_cross_kv_precompute", "ddit_denoise_step_cached", "ddit_linear_tile_count",
            "ddit_linear_tile_info", "ddit_linear_tile_choice", "ddit_linear_fwd_tile", "ddit_qk_norm_rope_fwd", "ddit_self_attn_fwd", "ddit_optimal_dop",
            "ddit_buddy_create", "ddit_buddy_alloc", "ddit_buddy_release", "ddit_buddy_free_gpus", "ddit_buddy_destroy",
-           "ddit_sched_simulate", "ddit_probe_mfma_bf16", "ddit_probe_stream_copy", "ddit_probe_residual_stream"]
+           "ddit_sched_simulate", "ddit_probe_mfma_bf16", "ddit_probe_stream_copy", "ddit_probe_stream_read", "ddit_probe_residual_stream"]
 
 
 class ddit_shape(C.Structure):
@@ -161,6 +161,7 @@ def _load() -> C.CDLL:
                                 C.c_int32, VP, VP, C.c_size_t, VP]
     lib.ddit_probe_mfma_bf16.argtypes = [VP, VP, C.c_int32, C.POINTER(C.c_double), VP]
     lib.ddit_probe_stream_copy.argtypes = [VP, VP, C.c_int64, VP]
+    lib.ddit_probe_stream_read.argtypes = [VP, C.c_int64, VP, VP]
     lib.ddit_probe_residual_stream.argtypes = [VP, VP, VP, VP, C.c_int64, C.c_int32, C.c_int32, VP]
     for n in EXPORTS:
         if n not in ("ddit_abi_version", "ddit_status_string", "ddit_last_error", "ddit_linear_tile_count"):
@@ -476,6 +477,10 @@ def ddit_probe_mfma_bf16(operands, sink, iters: int) -> float:
 
 def ddit_probe_stream_copy(src, dst, nbytes: int) -> None:
     _check(_lib.ddit_probe_stream_copy(_ptr(src), _ptr(dst), nbytes, _stream()))
+
+
+def ddit_probe_stream_read(src, nbytes: int, sink) -> None:
+    _check(_lib.ddit_probe_stream_read(_ptr(src), nbytes, _ptr(sink), _stream()))
 
 
 def ddit_probe_residual_stream(x, xh_out, o, gate, N: int, D: int, A: int) -> None:

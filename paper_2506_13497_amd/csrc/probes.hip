@@ -3,6 +3,7 @@
 //   ddit_probe_mfma_bf16       - a register-resident loop of v_mfma_f32_32x32x16_bf16 on operand data the
 //                                caller supplies (the chip's clock under matrix load depends on the data)
 //   ddit_probe_stream_copy     - a plain streaming copy of n bytes (16 bytes per lane, grid-stride)
+//   ddit_probe_stream_read     - the same bytes read only
 //   ddit_probe_residual_stream - the memory traffic of a k = A out-projection with gated residual update
 //                                (fp32 stream read and written, bf16 copy written, bf16 operand rows and a
 //                                gate vector read) and none of its matrix work: the floor such a launch
@@ -39,10 +40,33 @@ __global__ __launch_bounds__(256, 2) void k_probe_mfma(const bf16x8 *__restrict_
   out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// grid-stride over 16-byte pieces, four independent pieces in flight per thread
 __global__ __launch_bounds__(256) void k_probe_copy(const floatx4 *__restrict__ in, floatx4 *__restrict__ out, int64_t n16) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
-    __builtin_nontemporal_store(__builtin_nontemporal_load(in + i), out + i);
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const floatx4 a = __builtin_nontemporal_load(in + i), b = __builtin_nontemporal_load(in + i + stride),
+                  c = __builtin_nontemporal_load(in + i + 2 * stride), d = __builtin_nontemporal_load(in + i + 3 * stride);
+    __builtin_nontemporal_store(a, out + i);
+    __builtin_nontemporal_store(b, out + i + stride);
+    __builtin_nontemporal_store(c, out + i + 2 * stride);
+    __builtin_nontemporal_store(d, out + i + 3 * stride);
+  }
+  for (; i < n16; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(in + i), out + i);
+}
+
+// read-only stream: every thread adds up its pieces and leaves one float
+__global__ __launch_bounds__(256) void k_probe_read(const floatx4 *__restrict__ in, float *__restrict__ sink, int64_t n16) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  floatx4 s = {0.f, 0.f, 0.f, 0.f};
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const floatx4 a = __builtin_nontemporal_load(in + i), b = __builtin_nontemporal_load(in + i + stride),
+                  c = __builtin_nontemporal_load(in + i + 2 * stride), d = __builtin_nontemporal_load(in + i + 3 * stride);
+    s += (a + b) + (c + d);
+  }
+  for (; i < n16; i += stride) s += __builtin_nontemporal_load(in + i);
+  sink[(int64_t)blockIdx.x * blockDim.x + threadIdx.x] = (s[0] + s[1]) + (s[2] + s[3]);
 }
 
 // One wavefront per token row, rows dealt to wavefronts in consecutive runs of four; per row: read A bf16 of
@@ -105,6 +129,15 @@ int ddit_probe_stream_copy(const void *in, void *out, int64_t bytes, void *hip_s
   hipLaunchKernelGGL(k_probe_copy, dim3(blocks), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream),
                      reinterpret_cast<const floatx4 *>(in), reinterpret_cast<floatx4 *>(out), bytes / 16);
   return ddit::hip_fail(hipGetLastError(), "probe_copy launch");
+}
+
+int ddit_probe_stream_read(const void *in, int64_t bytes, float *sink, void *hip_stream) {
+  if (!in || !sink || bytes < 0 || bytes % 16) { set_error("probe_read: in, sink and a multiple of 16 bytes required"); return DDIT_ERR_INVALID_ARG; }
+  if (!al16(in) || !al16(sink)) { set_error("probe_read: pointers must be 16-byte aligned"); return DDIT_ERR_ALIGNMENT; }
+  const int blocks = 16 * ddit::device_cus();
+  hipLaunchKernelGGL(k_probe_read, dim3(blocks), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream),
+                     reinterpret_cast<const floatx4 *>(in), sink, bytes / 16);
+  return ddit::hip_fail(hipGetLastError(), "probe_read launch");
 }
 
 int ddit_probe_residual_stream(float *x, void *xh_out, const void *o, const float *gate, int64_t N, int32_t D, int32_t A,

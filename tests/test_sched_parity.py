@@ -164,3 +164,42 @@ def test_request_count_is_bounded(m):
     cfg = m.binding.ddit_sched_config(C.sizeof(m.binding.ddit_sched_config), 1, 1, 1, 1, 1, step, opt, None)
     assert lib.ddit_sched_simulate(C.byref(cfg), None, (1 << 22) + 1, None, None, 0, None, None) == m.DDIT_ERR_UNSUPPORTED
     assert "at most" in m.ddit_last_error()
+
+
+def _paper_printed():
+    """key -> value of tests/golden/paper_printed_values.txt (the few numbers the paper prints)."""
+    out = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "paper_printed_values.txt")):
+        line = line.split("#", 1)[0].strip()
+        if line:
+            k, v = line.split("=")
+            out[k.strip()] = float(v)
+    return out
+
+
+def test_paper_printed_B_and_step_count_on_the_measured_table(m):
+    """The paper prints B = 1, 2, 4 for 144p, 240p, 360p (section 4.2.3) and 30 denoising steps (section 6.1), found
+    on its own hardware.  On this library's measured table the same rule (largest change rate z) gives 2, 4, 4: one
+    MI355X is further from saturation at the low resolutions than the paper's GPU, so a doubling still pays where the
+    paper's no longer did.  Both sets of B drive the same scheduler: the library must agree with the oracle event for
+    event under either, and the paper's smaller groups must occupy no more GPU time per request."""
+    pv = _paper_printed()
+    paper_B = [int(pv["optimal_dop_144p"]), int(pv["optimal_dop_240p"]), int(pv["optimal_dop_360p"])]
+    steps = int(pv["denoising_steps"])
+    assert paper_B == [1, 2, 4] and steps == 30
+    ours_B = [so.optimal_dop(row) for row in MEASURED_US[:3]]
+    assert ours_B == [m.ddit_optimal_dop(row) for row in MEASURED_US[:3]] == [2, 4, 4]
+    assert all(p <= o for p, o in zip(paper_B, ours_B))
+    rng = random.Random(30)
+    t, reqs = 0.0, []
+    for _ in range(90):
+        t += rng.expovariate(2.0) * 1e6
+        reqs.append((int(t), rng.randrange(3)))
+    occ = {}
+    for name, B in (("paper", paper_B), ("ours", ours_B)):
+        case = dict(n_gpus=8, n_steps=steps, step_us=MEASURED_US[:3], opt_dop=B, requests=reqs, vae_us=[0, 0, 0], vae_gpus=1)
+        ora, got = run_both(m, case)
+        assert got == ora, name
+        check_invariants(case, *got)
+        occ[name] = got[2]["occupancy_gpu_us"]
+    assert occ["paper"] <= occ["ours"]      # smaller groups: less GPU time in total (Amdahl), at longer latency
