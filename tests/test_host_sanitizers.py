@@ -50,12 +50,11 @@ def exe(tmp_path_factory):
     with ThreadPoolExecutor(max_workers=min(8, len(b.SOURCES))) as ex:
         objs = list(ex.map(compile_one, b.SOURCES))
     main_obj = os.path.join(out, "host_checks_main.o")
-    r = subprocess.run([hipcc, "-O1", "-g", "-std=c++17", "-x", "c++", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
-                        "-fno-gpu-sanitize", "-c", os.path.join(ROOT, "tests", "host_checks_main.cpp"), "-o", main_obj],
-                       capture_output=True, text=True)
+    main_cmd = [hipcc, "-fno-gpu-sanitize", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-O1", "-g", "-std=c++17", "-x", "c++"]
+    r = subprocess.run(main_cmd + ["-c", os.path.join(ROOT, "tests", "host_checks_main.cpp"), "-o", main_obj], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-3000:]
-    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-fsanitize=address,undefined", "-fno-gpu-sanitize", "-o", path, main_obj, *objs],
-                       capture_output=True, text=True)
+    link_cmd = [hipcc, "-fno-gpu-sanitize", "-fsanitize=address,undefined", "--offload-arch=gfx950", "-o", path, main_obj, *objs]
+    r = subprocess.run(link_cmd, capture_output=True, text=True)
     assert r.returncode == 0, "link failed:\n" + r.stderr[-3000:]
     return path
 
