@@ -253,12 +253,15 @@ class Workload:
             e0.record()
             fn()
             e1.record()
-            records.append((group, e0, e1, flops, nbytes))
+            records.append((group, e0, e1, flops, nbytes, (kind_now[0], len(records) - layer_start[0])))
 
         lin = lambda n, k: 2.0 * N * n * k
 
+        kind_now, layer_start = [None], [0]
+
         def layer(kind, lw, keep):
             start = len(records)
+            kind_now[0], layer_start[0] = kind, start
             timed("modulated_layernorm", lambda: m.ddit_modulated_layernorm_fwd(x32, lw["ada_table"], c6, 0, L, 1e-6, xh),
                   nbytes=6.0 * N * D)
             timed("gemm_bf16", lambda: m.ddit_linear_fwd(m.DDIT_EPI_BF16, xh, D, lw["w_qkv"], lw["b_qkv"], N, 3 * A, D, qkv, 3 * A),
@@ -296,11 +299,20 @@ class Workload:
             if r % 4 == 3:   # keep the stream's values bounded over many passes (outside every event pair)
                 x32.normal_()
         torch.cuda.synchronize()
-        groups = {}
-        for group, e0, e1, flops, nbytes in records:
+        # a launch that took more than three times the median of its own place in the layer is a hiccup of the machine
+        # (seen once in dozens of runs: one launch of 68 ms among 15-us ones), not the kernel: it counts as the median
+        by_place = {}
+        for group, e0, e1, flops, nbytes, place in records:
+            by_place.setdefault(place, []).append(e0.elapsed_time(e1))
+        med = {place: sorted(v)[len(v) // 2] for place, v in by_place.items()}
+        groups, self.hiccups = {}, 0
+        for group, e0, e1, flops, nbytes, place in records:
             g = groups.setdefault(group, {"n": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
             g["n"] += 1
-            g["ms"] += e0.elapsed_time(e1)
+            ms_ = e0.elapsed_time(e1)
+            if ms_ > 3.0 * med[place]:
+                ms_, self.hiccups = med[place], self.hiccups + 1
+            g["ms"] += ms_
             g["flops"] += flops
             g["bytes"] += nbytes
         per_block = {k: g["n"] / reps for k, g in groups.items()}
@@ -482,6 +494,7 @@ def main():
         kernels, table_ms = w.kernel_table(reps)
         roofline = roofline_of(kernels, primary, w.gemm_tiles())
         roofline["sum_of_kernels_ms"] = round(table_ms, 2)
+        roofline["launches_taken_as_median"] = w.hiccups
         print("[bench] %s kernels (sum %.1f ms): %s" % (primary, table_ms, json.dumps(kernels)), file=sys.stderr, flush=True)
         denominators = probes(m, torch, sh)
         print("[bench] denominators: %s" % json.dumps(denominators), file=sys.stderr, flush=True)
@@ -632,6 +645,7 @@ def main():
             second["kernels"] = k5
             second["roofline"] = roofline_of(k5, "C5", w5.gemm_tiles())
             second["roofline"]["sum_of_kernels_ms"] = round(t5, 2)
+            second["roofline"]["launches_taken_as_median"] = w5.hiccups
             second["attention_stages"] = attention_stages(w5, lambda name: True)
             print("[bench] C5 kernels (sum %.1f ms): %s" % (t5, json.dumps(k5)), file=sys.stderr, flush=True)
             print("[bench] C5 attention: %s" % json.dumps(second["attention_stages"]), file=sys.stderr, flush=True)
